@@ -1,0 +1,192 @@
+/*
+ * csp.h — C ABI of the MI355X (gfx950) Cross-Self Pruning library.
+ *
+ * The library implements the KV-cache pruning pass of Cross-Self Pruning
+ * (arXiv 2412.04652, Section "Method", Algorithm 1) and the n-softmax decode
+ * attention over the pruned cache (Section "Smoothness recovery of attention
+ * scores").  One call per step of the path:
+ *
+ *   csp_score        observation-window attention weights, summed per key and
+ *                    split into intra- / inter-modality importance
+ *   csp_select       budget rule, per-region top-K, union with the recent keys
+ *   csp_compact      gather of the kept K/V rows into the pruned cache
+ *   csp_decode_attn  one decode step of n-softmax attention over that cache
+ *   csp_append_kv    append the new token's k, v to the pruned cache
+ *
+ * Conventions
+ *  - "device" pointers are HIP device memory owned by the caller; "host"
+ *    pointers are ordinary host memory.  The library never allocates, frees or
+ *    retains memory and never synchronises the host: every call enqueues its
+ *    kernels on `stream` (a hipStream_t passed as void*; NULL = the default
+ *    stream) and returns.  Scratch memory is passed in by the caller, sized by
+ *    the *_workspace_bytes functions (pure host functions).
+ *  - Outputs must not alias inputs.
+ *  - Return value: CSP_OK, or a negative error code.  Arguments are validated
+ *    on the host before anything is launched, so a call that returns an error
+ *    has launched nothing.  CSP_EHIP means a HIP launch failed; the HIP error
+ *    stays readable through hipGetLastError().
+ *  - Q/K/V element type: CSP_BF16 (2 bytes) or CSP_F32.  Rows of D elements are
+ *    contiguous; D is 64 or 128; every row must start on a 16-byte boundary.
+ *    All arithmetic accumulates in fp32.
+ *  - Sequences are packed along the token axis: sequence b owns tokens
+ *    cu_seqlens[b] .. cu_seqlens[b+1]-1 (ragged batches); key row (token t,
+ *    KV head h) starts at element  t*k_stride_tok + h*k_stride_head.
+ *  - Query head hq reads KV head hq / (H_q/H_kv).  A *selection group* is
+ *    sel_group consecutive query heads whose scores are summed before the
+ *    top-K (head-axis handling of Section "Cross-self pruning"): 1 = one index
+ *    set per head (requires H_q == H_kv), H_q/H_kv = one per KV head, H_q =
+ *    one per layer.  sel_group must be a multiple of H_q/H_kv and divide H_q.
+ *    H_sel = H_q / sel_group.
+ */
+#ifndef CSP_H
+#define CSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { CSP_BF16 = 0, CSP_F32 = 1 };
+
+enum {
+    CSP_OK = 0,
+    CSP_EINVAL = -1,       /* null pointer, inconsistent sizes, bad stride or alignment */
+    CSP_EUNSUPPORTED = -2, /* D or dtype the kernels are not built for */
+    CSP_EWORKSPACE = -3,   /* workspace missing or too small */
+    CSP_EHIP = -4          /* a HIP call failed */
+};
+
+/* Problem description shared by all calls (plain data; the library reads it
+ * during the call only). */
+typedef struct csp_desc {
+    int32_t dtype;       /* CSP_BF16 | CSP_F32: type of Q, K, V and of the pruned cache */
+    int32_t B;           /* sequences in the batch */
+    int32_t H_q, H_kv;   /* query heads, KV heads (H_q % H_kv == 0) */
+    int32_t D;           /* head dimension: 64 or 128 */
+    int32_t sel_group;   /* query heads per selection group (see above) */
+    int32_t window_O;    /* observation window: the last O queries (A[-O:, :-R]) */
+    int32_t recent_R;    /* recent keys always kept and never ranked */
+    int32_t causal;      /* 1: window query at position p sees keys j <= p; 0: sees all */
+    int32_t max_seqlen;  /* >= every sequence length (sizes grids and workspaces) */
+    double  n_score;     /* n of the n-softmax used for scoring; 0 = plain softmax */
+    double  n_decode;    /* n of the n-softmax used by csp_decode_attn (paper: 1) */
+    double  cross_ratio; /* share of the T-R selected keys given to the inter-modality
+                            region (appendix table "Cross Ratio"); in [0,1] */
+    const int32_t* cu_seqlens_host; /* host   int32[B+1], for validation and sizing */
+    const int32_t* budget_T_host;   /* host   int32[B], maximum cache length T per sequence */
+    const int32_t* cu_seqlens;      /* device int32[B+1], same values */
+    const int32_t* budget_T;        /* device int32[B], same values */
+    int64_t k_stride_tok, k_stride_head; /* elements */
+    int64_t v_stride_tok, v_stride_head; /* elements */
+} csp_desc;
+
+/* Human-readable name of an error code (static string). */
+const char* csp_strerror(int code);
+
+/* Library version string (static). */
+const char* csp_version(void);
+
+/* ------------------------------------------------------------------------
+ * csp_score — Eq. "A = softmax(QK^T/sqrt d)" (or Eq. "n-softmax" when
+ * n_score > 0) for the last O queries against every cached key, then the
+ * per-key sums over the query axis split by modality, Eq. "cross-self":
+ *   score_self [s][t]  = sum over the group's heads and over window rows i
+ *                        whose modality equals the key's, of A_ij
+ *   score_cross[s][t]  = same over rows of the other modality
+ * for prefix keys j < L-R (t = cu_seqlens[b] + j); entries of the last R keys
+ * of each sequence are written as 0.  The softmax denominator runs over all
+ * visible keys including the last R.
+ *
+ *   q_win     device [B][H_q][O][D]  queries of positions L_b-O .. L_b-1
+ *   k         device keys, strides from the descriptor
+ *   modality  device uint8[total_tokens], 0 = text, 1 = visual
+ *   score_*   device float [H_sel][total_tokens]
+ *   ws        device scratch of csp_score_workspace_bytes(desc) bytes, 16-byte aligned
+ * Requires O <= L_b and R <= L_b for every sequence (CSP_EINVAL otherwise);
+ * O <= 128.
+ * ---------------------------------------------------------------------- */
+size_t csp_score_workspace_bytes(const csp_desc* desc);
+int csp_score(const csp_desc* desc, const void* q_win, const void* k, const uint8_t* modality,
+              float* score_self, float* score_cross, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * csp_select — Eq. "top-K" per region, the mask combination (read as the
+ * union of the two independently selected sets), the recent keys of the
+ * cache-construction equation, and Algorithm 1's early-out.
+ *
+ * Per sequence b and selection group s, with L = L_b, T = budget_T[b]:
+ *  - L <= T: identity, kept = 0..L-1.
+ *  - otherwise K_sel = T-R, K^c = floor(cross_ratio*K_sel), K^s = K_sel-K^c;
+ *    candidates of the self region are prefix keys whose modality some window
+ *    query shares, of the cross region prefix keys whose other modality some
+ *    window query has; a region with fewer candidates than its share passes
+ *    the excess to the other.  The K^s largest score_self among self
+ *    candidates and the K^c largest score_cross among cross candidates are
+ *    kept (ties: lower index first), plus positions L-R..L-1.
+ *
+ *   kept_idx  device int32 [B][H_sel][kept_cap]: kept positions within the
+ *             sequence, ascending, unique; slots past the count hold -1
+ *   kept_cap  >= min(T_b, L_b) for every b (CSP_EINVAL otherwise)
+ *   kept_cnt  device int32 [B][H_sel][4]: {kept, K^s, K^c, keys in both masks}
+ * With a single-modality window (the usual case) kept == min(T, L); a window
+ * holding both modalities can select a key twice and keeps fewer.
+ * T_b < R with L_b > T_b is CSP_EINVAL.  Scores must be >= 0 (they are sums
+ * of probabilities); selection compares their fp32 bit patterns.
+ * No workspace is needed: ws may be NULL.
+ * ---------------------------------------------------------------------- */
+size_t csp_select_workspace_bytes(const csp_desc* desc);
+int csp_select(const csp_desc* desc, const float* score_self, const float* score_cross,
+               const uint8_t* modality, int32_t* kept_idx, int32_t kept_cap, int32_t* kept_cnt,
+               void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * csp_compact — cache construction, Eq. "K = (K.M) (+) K[-R:]": a bit copy
+ *   k_out[b][h][t] = k[cu_seqlens[b] + kept_idx[b][s(h)][t]][h],  t < kept
+ * (same for v), s(h) = selection group of KV head h.  Row (b, h, t) of the
+ * output starts at element b*out_stride_b + h*out_stride_head + t*out_stride_tok;
+ * the caller sizes it for kept_cap plus the tokens it will append.
+ *   kv_len    device int32 [B][H_kv], receives the kept count (may be NULL)
+ * ---------------------------------------------------------------------- */
+int csp_compact(const csp_desc* desc, const void* k, const void* v, const int32_t* kept_idx,
+                int32_t kept_cap, const int32_t* kept_cnt, void* k_out, void* v_out,
+                int64_t out_stride_b, int64_t out_stride_head, int64_t out_stride_tok,
+                int32_t* kv_len, void* stream);
+
+/* ------------------------------------------------------------------------
+ * csp_decode_attn — one decode step with Eq. "n-softmax":
+ *   s_t = q.k_t / sqrt(D),  p_t = e^{s_t} / (n_decode + sum_u e^{s_u}),
+ *   out = sum_t p_t v_t      over t < kv_len[b][h]; no causal mask.
+ * n enters once per query head, scaled consistently with the running maximum
+ * (it is a virtual key of logit ln n and zero value).
+ *
+ *   q         device [B][H_q][D] (dtype of the descriptor)
+ *   k_cache, v_cache  device, row (b, h, t) at b*cache_stride_b +
+ *             h*cache_stride_head + t*cache_stride_tok (elements)
+ *   kv_len    device int32 [B][H_kv]
+ *   max_kv_len  host upper bound on kv_len (sizes the split of the key axis)
+ *   out       device float [B][H_q][D]
+ *   ws        device scratch of csp_decode_workspace_bytes(desc, max_kv_len) bytes
+ * kv_len == 0 gives out = 0.
+ * ---------------------------------------------------------------------- */
+size_t csp_decode_workspace_bytes(const csp_desc* desc, int32_t max_kv_len);
+int csp_decode_attn(const csp_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                    int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                    const int32_t* kv_len, int32_t max_kv_len, float* out,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * csp_append_kv — the KV-cache append of Section "Preliminary": writes the new
+ * token's key and value (device [B][H_kv][D]) at row kv_len[b][h] of the
+ * pruned cache and increments kv_len[b][h].  cache_cap is the number of rows
+ * each (b, h) slab can hold; a full slab is left unchanged.
+ * ---------------------------------------------------------------------- */
+int csp_append_kv(const csp_desc* desc, const void* k_new, const void* v_new, void* k_cache,
+                  void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                  int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CSP_H */

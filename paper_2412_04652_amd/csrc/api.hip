@@ -1,0 +1,224 @@
+// C ABI of libcsp: host-side validation and marshalling (see include/csp.h for
+// the contract of every entry point).  Nothing here touches the GPU until the
+// arguments have been checked.
+#include <cmath>
+#include <cstring>
+
+#include "csp_internal.h"
+
+using namespace csp;
+
+namespace {
+
+struct Checked {
+    int G, H_sel, kv_per_sel, EB, row_bytes;
+    int64_t total_tokens;
+    int max_len;
+};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Checks of the descriptor that every call shares.  need_lengths: the call
+// reads cu_seqlens (everything but decode/append).
+int check_desc(const csp_desc* d, bool need_lengths, Checked* c) {
+    if (!d) return CSP_EINVAL;
+    if (d->dtype != CSP_BF16 && d->dtype != CSP_F32) return CSP_EUNSUPPORTED;
+    if (d->D != 64 && d->D != 128) return CSP_EUNSUPPORTED;
+    if (d->B <= 0 || d->H_q <= 0 || d->H_kv <= 0 || d->H_q % d->H_kv != 0) return CSP_EINVAL;
+    if (d->B > 32767) return CSP_EINVAL;
+    c->G = d->H_q / d->H_kv;
+    if (d->sel_group <= 0 || d->H_q % d->sel_group != 0 || d->sel_group % c->G != 0) return CSP_EINVAL;
+    c->H_sel = d->H_q / d->sel_group;
+    c->kv_per_sel = d->sel_group / c->G;
+    c->EB = d->dtype == CSP_BF16 ? 2 : 4;
+    c->row_bytes = d->D * c->EB;
+    c->total_tokens = 0;
+    c->max_len = 0;
+    if (!(d->n_score >= 0.0) || !(d->n_decode >= 0.0) || !std::isfinite(d->n_score) || !std::isfinite(d->n_decode)) return CSP_EINVAL;
+    if (!(d->cross_ratio >= 0.0 && d->cross_ratio <= 1.0)) return CSP_EINVAL;
+    if (need_lengths) {
+        if (!d->cu_seqlens_host || !d->cu_seqlens) return CSP_EINVAL;
+        if (d->window_O <= 0 || d->recent_R < 0) return CSP_EINVAL;
+        if (d->window_O > 128) return CSP_EUNSUPPORTED;
+        if (d->cu_seqlens_host[0] != 0) return CSP_EINVAL;
+        for (int b = 0; b < d->B; ++b) {
+            const int64_t len = (int64_t)d->cu_seqlens_host[b + 1] - d->cu_seqlens_host[b];
+            if (len <= 0 || len > d->max_seqlen) return CSP_EINVAL;
+            if (d->window_O > len || d->recent_R > len) return CSP_EINVAL;
+            if (len > c->max_len) c->max_len = (int)len;
+        }
+        c->total_tokens = d->cu_seqlens_host[d->B];
+    }
+    return CSP_OK;
+}
+
+int check_kv_strides(int64_t s_tok, int64_t s_head, int D, int EB) {
+    if (s_tok < D || s_head < 0) return CSP_EINVAL;
+    if ((s_tok * EB) % 16 != 0 || (s_head * EB) % 16 != 0) return CSP_EINVAL;
+    return CSP_OK;
+}
+
+int check_budgets(const csp_desc* d, int kept_cap) {
+    if (!d->budget_T_host || !d->budget_T) return CSP_EINVAL;
+    for (int b = 0; b < d->B; ++b) {
+        const int len = d->cu_seqlens_host[b + 1] - d->cu_seqlens_host[b];
+        const int T = d->budget_T_host[b];
+        if (T < 0) return CSP_EINVAL;
+        if (len > T && T < d->recent_R) return CSP_EINVAL;
+        if ((len < T ? len : T) > kept_cap) return CSP_EINVAL;
+    }
+    return CSP_OK;
+}
+
+const double kLog2e = 1.4426950408889634;
+
+}  // namespace
+
+extern "C" {
+
+const char* csp_strerror(int code) {
+    switch (code) {
+        case CSP_OK: return "ok";
+        case CSP_EINVAL: return "invalid argument";
+        case CSP_EUNSUPPORTED: return "unsupported head dimension, dtype or window size";
+        case CSP_EWORKSPACE: return "workspace missing or too small";
+        case CSP_EHIP: return "HIP call failed";
+        default: return "unknown error";
+    }
+}
+
+const char* csp_version(void) { return "csp-gfx950 0.1"; }
+
+size_t csp_score_workspace_bytes(const csp_desc* d) {
+    Checked c;
+    if (!d || d->B <= 0 || d->H_q <= 0 || d->max_seqlen <= 0 || d->window_O <= 0) return 0;
+    const int ck = score_chunk_keys(d->B, d->H_q, d->max_seqlen);
+    const size_t n_chunks = (size_t)(d->max_seqlen + ck - 1) / ck;
+    (void)c;
+    return (size_t)d->B * d->H_q * n_chunks * d->window_O * 2 * sizeof(float);
+}
+
+int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t* modality,
+              float* score_self, float* score_cross, void* ws, size_t ws_bytes, void* stream) {
+    Checked c;
+    int rc = check_desc(d, true, &c);
+    if (rc != CSP_OK) return rc;
+    if (!q_win || !k || !modality || !score_self || !score_cross) return CSP_EINVAL;
+    if (!aligned16(q_win) || !aligned16(k)) return CSP_EINVAL;
+    if ((rc = check_kv_strides(d->k_stride_tok, d->k_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    const size_t need = csp_score_workspace_bytes(d);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return CSP_EWORKSPACE;
+
+    ScoreParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.q_win = q_win; p.k = k; p.modality = modality;
+    p.score_self = score_self; p.score_cross = score_cross;
+    p.part = static_cast<float*>(ws);
+    p.cu = d->cu_seqlens;
+    p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
+    p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
+    p.chunk_keys = score_chunk_keys(d->B, d->H_q, d->max_seqlen);
+    p.n_chunks = (d->max_seqlen + p.chunk_keys - 1) / p.chunk_keys;
+    p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
+    p.total_tokens = c.total_tokens;
+    p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
+    p.n_score = (float)d->n_score;
+    return launch_score(p, d->dtype, d->D, d->max_seqlen, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+size_t csp_select_workspace_bytes(const csp_desc*) { return 0; }
+
+int csp_select(const csp_desc* d, const float* score_self, const float* score_cross,
+               const uint8_t* modality, int32_t* kept_idx, int32_t kept_cap, int32_t* kept_cnt,
+               void* /*ws*/, size_t /*ws_bytes*/, void* stream) {
+    Checked c;
+    int rc = check_desc(d, true, &c);
+    if (rc != CSP_OK) return rc;
+    if (!score_self || !score_cross || !modality || !kept_idx || !kept_cnt || kept_cap <= 0) return CSP_EINVAL;
+    if ((rc = check_budgets(d, kept_cap)) != CSP_OK) return rc;
+    SelectParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.score_self = score_self; p.score_cross = score_cross; p.modality = modality;
+    p.cu = d->cu_seqlens; p.budget_T = d->budget_T;
+    p.kept_idx = kept_idx; p.kept_cnt = kept_cnt;
+    p.B = d->B; p.H_sel = c.H_sel; p.O = d->window_O; p.R = d->recent_R; p.kept_cap = kept_cap;
+    p.total_tokens = c.total_tokens;
+    p.cross_ratio = d->cross_ratio;
+    return launch_select(p, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+int csp_compact(const csp_desc* d, const void* k, const void* v, const int32_t* kept_idx,
+                int32_t kept_cap, const int32_t* kept_cnt, void* k_out, void* v_out,
+                int64_t out_stride_b, int64_t out_stride_head, int64_t out_stride_tok,
+                int32_t* kv_len, void* stream) {
+    Checked c;
+    int rc = check_desc(d, true, &c);
+    if (rc != CSP_OK) return rc;
+    if (!k || !v || !kept_idx || !kept_cnt || !k_out || !v_out || kept_cap <= 0) return CSP_EINVAL;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return CSP_EINVAL;
+    if ((rc = check_kv_strides(d->k_stride_tok, d->k_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    if ((rc = check_kv_strides(d->v_stride_tok, d->v_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    if ((rc = check_kv_strides(out_stride_tok, out_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    if (out_stride_b < 0 || (out_stride_b * c.EB) % 16 != 0) return CSP_EINVAL;
+    CompactParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.k = k; p.v = v; p.kept_idx = kept_idx; p.kept_cnt = kept_cnt; p.cu = d->cu_seqlens;
+    p.k_out = k_out; p.v_out = v_out; p.kv_len = kv_len;
+    p.B = d->B; p.H_kv = d->H_kv; p.H_sel = c.H_sel; p.kv_per_sel = c.kv_per_sel; p.kept_cap = kept_cap;
+    p.k_stride_tok = d->k_stride_tok * c.EB; p.k_stride_head = d->k_stride_head * c.EB;
+    p.v_stride_tok = d->v_stride_tok * c.EB; p.v_stride_head = d->v_stride_head * c.EB;
+    p.out_stride_b = out_stride_b * c.EB; p.out_stride_head = out_stride_head * c.EB; p.out_stride_tok = out_stride_tok * c.EB;
+    return launch_compact(p, c.row_bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+size_t csp_decode_workspace_bytes(const csp_desc* d, int32_t max_kv_len) {
+    if (!d || d->B <= 0 || d->H_q <= 0 || d->H_kv <= 0 || max_kv_len <= 0) return 0;
+    const int ns = decode_num_splits(d->B, d->H_kv, max_kv_len);
+    return (size_t)d->B * d->H_q * ns * (d->D + 2) * sizeof(float);
+}
+
+int csp_decode_attn(const csp_desc* d, const void* q, const void* k_cache, const void* v_cache,
+                    int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                    const int32_t* kv_len, int32_t max_kv_len, float* out,
+                    void* ws, size_t ws_bytes, void* stream) {
+    Checked c;
+    int rc = check_desc(d, false, &c);
+    if (rc != CSP_OK) return rc;
+    if (!q || !k_cache || !v_cache || !kv_len || !out || max_kv_len <= 0) return CSP_EINVAL;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return CSP_EINVAL;
+    if ((rc = check_kv_strides(cache_stride_tok, cache_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    if (cache_stride_b < 0 || (cache_stride_b * c.EB) % 16 != 0) return CSP_EINVAL;
+    const size_t need = csp_decode_workspace_bytes(d, max_kv_len);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return CSP_EWORKSPACE;
+    DecodeParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.q = q; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_len = kv_len; p.out = out;
+    p.part = static_cast<float*>(ws);
+    p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.G = c.G;
+    p.n_splits = decode_num_splits(d->B, d->H_kv, max_kv_len);
+    p.max_kv_len = max_kv_len;
+    p.stride_b = cache_stride_b * c.EB; p.stride_head = cache_stride_head * c.EB; p.stride_tok = cache_stride_tok * c.EB;
+    p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
+    p.n_decode = (float)d->n_decode;
+    return launch_decode(p, d->dtype, d->D, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+int csp_append_kv(const csp_desc* d, const void* k_new, const void* v_new, void* k_cache,
+                  void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                  int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, void* stream) {
+    Checked c;
+    int rc = check_desc(d, false, &c);
+    if (rc != CSP_OK) return rc;
+    if (!k_new || !v_new || !k_cache || !v_cache || !kv_len || cache_cap <= 0) return CSP_EINVAL;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_cache) || !aligned16(v_cache)) return CSP_EINVAL;
+    if ((rc = check_kv_strides(cache_stride_tok, cache_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    if (cache_stride_b < 0 || (cache_stride_b * c.EB) % 16 != 0) return CSP_EINVAL;
+    AppendParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_len = kv_len;
+    p.B = d->B; p.H_kv = d->H_kv; p.cache_cap = cache_cap; p.row_bytes = c.row_bytes;
+    p.stride_b = cache_stride_b * c.EB; p.stride_head = cache_stride_head * c.EB; p.stride_tok = cache_stride_tok * c.EB;
+    return launch_append(p, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,459 @@
+// csp_score kernels for gfx950.
+//
+// What is computed (paper: Eq. "A = softmax(QK^T/sqrt d)" / Eq. "n-softmax",
+// the window trim A[-O:, :-R], Eq. "cross-self"): for the last O queries of a
+// sequence, attention weights over every cached key, then per-key sums over
+// the query axis split by whether query and key share a modality.
+//
+// Design.  The per-key sums need the final softmax normaliser of every window
+// row, which depends on all L keys, so the key stream is walked twice:
+//   pass A (score_stats_kernel)  : S = K Q^T on MFMA with queries on the lane
+//        axis, so the running (max, sum-exp) of a row lives in one lane and
+//        needs no cross-lane traffic inside the loop;
+//   pass B (score_colsum_kernel) : S = Q K^T with keys on the lane axis, so
+//        the sum over queries of exp(S - lse) is an in-lane add chain.
+// The two orientations use the same LDS tile and the same register fragments;
+// only the operand order of the MFMA differs.
+// A workgroup is 4 wavefronts; each wavefront owns a contiguous run of keys of
+// the workgroup's chunk and streams it in tiles of 32 keys: coalesced 16-byte
+// global loads (4 full 256-byte rows per instruction for bf16/D=128) into
+// registers one tile ahead, a wave-private padded LDS tile as the transpose
+// between the load layout and the MFMA operand layout, no workgroup barrier
+// in the loop.  All exponentials are base 2 with log2(e)/sqrt(D) folded into
+// one FMA per element.
+#include "csp_internal.h"
+
+namespace csp {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
+
+template <typename E, int D>
+struct Geom {
+    static constexpr int EB = elem_bytes<E>::value;
+    static constexpr int ROW_BYTES = D * EB;
+    static constexpr int ROW_STRIDE = ROW_BYTES + 16;  // +16 B: conflict-free 16-byte LDS reads down a column
+    static constexpr int CPR = ROW_BYTES / 16;         // 16-byte chunks per row
+    static constexpr int RPI = kWave / CPR;            // rows covered by one wavefront load instruction
+    static constexpr int NLD = kTile / RPI;            // load instructions per tile
+    static constexpr int KSTEP = (EB == 2) ? 16 : 2;   // contraction depth of one MFMA
+    static constexpr int NK = D / KSTEP;
+    static constexpr int TILE_LDS = kTile * ROW_STRIDE;
+    static constexpr int QSTRIDE = D + 4;              // floats; fp32 queries staged in LDS
+};
+
+__device__ __forceinline__ f32x16 mma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x16 mma(float a, float b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// Orders LDS writes of some lanes before LDS reads of other lanes of the same
+// wavefront (the tile is wave-private, so no workgroup barrier is needed).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- query fragments --------------------------------------------------------
+// MFMA operand layout (32 x KSTEP block): lane = (r = lane%32, half = lane/32)
+// holds row r, contraction elements [s*KSTEP + half*KSTEP/2, +KSTEP/2).
+template <typename E, int D, int NQB>
+struct QFrags;
+
+template <int D, int NQB>
+struct QFrags<bf16_tag, D, NQB> {
+    bf16x8 f[NQB][D / 16];
+    // qhead: [O][D] bf16 of one head.  Rows >= O read as zero.
+    __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* /*q_lds*/) {
+        const int lane = tid & 63, r = lane & 31, half = lane >> 5;
+#pragma unroll
+        for (int nb = 0; nb < NQB; ++nb)
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                const int row = nb * 32 + r;
+                u32x4 w = {0u, 0u, 0u, 0u};
+                if (row < O) w = *reinterpret_cast<const u32x4*>(qhead + ((size_t)row * D + s * 16 + half * 8) * 2);
+                f[nb][s] = __builtin_bit_cast(bf16x8, w);
+            }
+    }
+    __device__ __forceinline__ bf16x8 get(int nb, int s, int /*lane*/, const float* /*q_lds*/) const { return f[nb][s]; }
+    static constexpr bool kUsesLds = false;
+};
+
+template <int D, int NQB>
+struct QFrags<f32_tag, D, NQB> {
+    // fp32 queries are staged in LDS by the whole workgroup (caller barriers).
+    __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* q_lds) {
+        constexpr int C4 = D / 4;
+        for (int idx = tid; idx < NQB * 32 * C4; idx += kThreads) {
+            const int row = idx / C4, c4 = idx % C4;
+            float4 w = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < O) w = *reinterpret_cast<const float4*>(qhead + ((size_t)row * D + c4 * 4) * 4);
+            *reinterpret_cast<float4*>(q_lds + row * Geom<f32_tag, D>::QSTRIDE + c4 * 4) = w;
+        }
+    }
+    __device__ __forceinline__ float get(int nb, int s, int lane, const float* q_lds) const {
+        return q_lds[(nb * 32 + (lane & 31)) * Geom<f32_tag, D>::QSTRIDE + s * 2 + (lane >> 5)];
+    }
+    static constexpr bool kUsesLds = true;
+};
+
+template <typename E, int D>
+__device__ __forceinline__ auto k_frag(const char* tile, int s, int lane) {
+    using G = Geom<E, D>;
+    const int r = lane & 31, half = lane >> 5;
+    if constexpr (G::EB == 2) {
+        return *reinterpret_cast<const bf16x8*>(tile + r * G::ROW_STRIDE + s * 32 + half * 16);
+    } else {
+        return *reinterpret_cast<const float*>(tile + r * G::ROW_STRIDE + (s * 2 + half) * 4);
+    }
+}
+
+// Global -> registers: tile rows j0 .. j0+31 of one (sequence, KV head); rows
+// past the end of the sequence re-read row L-1 (masked by the caller).
+template <typename E, int D>
+__device__ __forceinline__ void load_tile(u32x4 (&st)[(Geom<E, D>::NLD)], const char* kbase, int64_t tok_bytes,
+                                          int j0, int L, int lane) {
+    using G = Geom<E, D>;
+#pragma unroll
+    for (int i = 0; i < G::NLD; ++i) {
+        int j = j0 + i * G::RPI + lane / G::CPR;
+        j = j < L ? j : L - 1;
+        st[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)j * tok_bytes + (lane % G::CPR) * 16);
+    }
+}
+
+template <typename E, int D>
+__device__ __forceinline__ void store_tile(const u32x4 (&st)[(Geom<E, D>::NLD)], char* tile, int lane) {
+    using G = Geom<E, D>;
+#pragma unroll
+    for (int i = 0; i < G::NLD; ++i)
+        *reinterpret_cast<u32x4*>(tile + (i * G::RPI + lane / G::CPR) * G::ROW_STRIDE + (lane % G::CPR) * 16) = st[i];
+}
+
+// key / query index of accumulator register v of a 32x32 MFMA result for the
+// register-indexed axis (the other axis is lane%32)
+__device__ __forceinline__ int acc_row(int v, int half) { return (v >> 2) * 8 + half * 4 + (v & 3); }
+
+template <typename E, int D, int NQB>
+struct Smem {
+    using G = Geom<E, D>;
+    static constexpr int kTiles = kWaves * G::TILE_LDS;
+    static constexpr int kRed = kWaves * NQB * 32 * 8;    // float2 per (wave, query)
+    static constexpr int kNlse = NQB * 32 * 4;
+    static constexpr int kWq = NQB * 32;                   // uint8 modality of window rows
+    static constexpr int kQ = QFrags<E, D, NQB>::kUsesLds ? NQB * 32 * G::QSTRIDE * 4 : 0;
+    static constexpr int off_red = kTiles;
+    static constexpr int off_nlse = off_red + kRed;
+    static constexpr int off_wq = off_nlse + kNlse;
+    static constexpr int off_q = (off_wq + kWq + 15) & ~15;
+    static constexpr int total = off_q + kQ;
+};
+
+// ---------------------------------------------------------------------------
+// Pass A: per (sequence, query head, chunk) partial row statistics.
+// ---------------------------------------------------------------------------
+template <typename E, int D, int NQB>
+__global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreParams p) {
+    using G = Geom<E, D>;
+    using SM = Smem<E, D, NQB>;
+    extern __shared__ __align__(16) char smem[];
+    const int chunk = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+    const int seq0 = p.cu[b];
+    const int L = p.cu[b + 1] - seq0;
+    const int c0 = chunk * p.chunk_keys;
+    if (c0 >= L) return;
+    const int O = p.O;
+    const float c = p.scale_log2;
+    const float NEG_INF = -__builtin_inff();
+
+    char* tile = smem + wave * G::TILE_LDS;
+    float2* red = reinterpret_cast<float2*>(smem + SM::off_red);
+    float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
+
+    QFrags<E, D, NQB> qf;
+    qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
+    if constexpr (QFrags<E, D, NQB>::kUsesLds) __syncthreads();
+
+    const int hk = hq / p.G;
+    const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
+    const int64_t tok_bytes = p.k_stride_tok * G::EB;
+
+    const int cpw = p.chunk_keys / kWaves;
+    const int jb = c0 + wave * cpw;
+    const int je = min(jb + cpw, L);
+    const int ntiles = je > jb ? (je - jb + kTile - 1) / kTile : 0;
+
+    float m_run[NQB], l_run[NQB];
+    int pos_q[NQB];  // absolute position of this lane's query in block nb
+#pragma unroll
+    for (int nb = 0; nb < NQB; ++nb) {
+        m_run[nb] = NEG_INF;
+        l_run[nb] = 0.f;
+        pos_q[nb] = L - O + nb * 32 + (lane & 31);
+    }
+    const int mask_from = p.causal ? L - O : L;  // keys below this index are visible to every row
+
+    u32x4 st[G::NLD];
+    if (ntiles > 0) load_tile<E, D>(st, kbase, tok_bytes, jb, L, lane);
+    for (int t = 0; t < ntiles; ++t) {
+        const int j0 = jb + t * kTile;
+        wave_lds_sync();
+        store_tile<E, D>(st, tile, lane);
+        wave_lds_sync();
+        if (t + 1 < ntiles) load_tile<E, D>(st, kbase, tok_bytes, j0 + kTile, L, lane);
+
+        f32x16 acc[NQB];
+#pragma unroll
+        for (int nb = 0; nb < NQB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < G::NK; ++s) {
+            const auto kf = k_frag<E, D>(tile, s, lane);
+#pragma unroll
+            for (int nb = 0; nb < NQB; ++nb) acc[nb] = mma(kf, qf.get(nb, s, lane, q_lds), acc[nb]);
+        }
+        // acc[nb][v]: key j0 + acc_row(v, half), query nb*32 + lane%32
+        const bool need_mask = j0 + kTile > mask_from;
+#pragma unroll
+        for (int nb = 0; nb < NQB; ++nb) {
+            float mx = NEG_INF;
+            if (need_mask) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int j = j0 + acc_row(v, half);
+                    const bool ok = j < L && (!p.causal || j <= pos_q[nb]);
+                    acc[nb][v] = ok ? acc[nb][v] : NEG_INF;
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[nb][v]);
+            const float mnew = fmaxf(m_run[nb], mx * c);
+            const float msafe = mnew == NEG_INF ? 0.f : mnew;
+            float sum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(acc[nb][v], c, -msafe));
+            l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - msafe) + sum;
+            m_run[nb] = mnew;
+        }
+    }
+
+    // combine the two lane halves, then the four wavefronts
+#pragma unroll
+    for (int nb = 0; nb < NQB; ++nb) {
+        const float mo = __shfl_xor(m_run[nb], 32);
+        const float lo = __shfl_xor(l_run[nb], 32);
+        const float M = fmaxf(m_run[nb], mo);
+        const float Ms = M == NEG_INF ? 0.f : M;
+        const float Lc = l_run[nb] * fast_exp2(m_run[nb] - Ms) + lo * fast_exp2(mo - Ms);
+        if (half == 0) red[wave * (NQB * 32) + nb * 32 + lane] = make_float2(M, Lc);
+    }
+    __syncthreads();
+    if (tid < O) {
+        float M = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, red[w * (NQB * 32) + tid].x);
+        const float Ms = M == NEG_INF ? 0.f : M;
+        float Lc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float2 r = red[w * (NQB * 32) + tid];
+            Lc += r.y * fast_exp2(r.x - Ms);
+        }
+        float2* out = reinterpret_cast<float2*>(p.part) + ((size_t)(b * p.H_q + hq) * p.n_chunks + chunk) * O + tid;
+        *out = make_float2(M, Lc);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Pass B: per (sequence, selection group, chunk) column sums.
+// ---------------------------------------------------------------------------
+template <typename E, int D, int NQB>
+__global__ __launch_bounds__(kThreads) void score_colsum_kernel(ScoreParams p) {
+    using G = Geom<E, D>;
+    using SM = Smem<E, D, NQB>;
+    extern __shared__ __align__(16) char smem[];
+    const int chunk = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+    const int seq0 = p.cu[b];
+    const int L = p.cu[b + 1] - seq0;
+    const int c0 = chunk * p.chunk_keys;
+    if (c0 >= L) return;
+    const int O = p.O, R = p.R;
+    const float c = p.scale_log2;
+    const float NEG_INF = -__builtin_inff();
+    const int n_chunks_b = (L + p.chunk_keys - 1) / p.chunk_keys;
+
+    char* tile = smem + wave * G::TILE_LDS;
+    float* nlse_s = reinterpret_cast<float*>(smem + SM::off_nlse);
+    uint8_t* wq = reinterpret_cast<uint8_t*>(smem + SM::off_wq);
+    float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
+
+    // modality of the window rows; a window with one modality takes the fast path
+    if (tid < NQB * 32) wq[tid] = tid < O ? (p.modality[seq0 + L - O + tid] ? 1 : 0) : 2;
+    __syncthreads();
+    bool any_text = false, any_vis = false;
+    for (int i = 0; i < O; ++i) {
+        any_text |= wq[i] == 0;
+        any_vis |= wq[i] == 1;
+    }
+    const bool mixed = any_text && any_vis;
+    // bit (mb*16+v) set: the query of accumulator (mb, v) is a text query
+    uint32_t text_bits[(NQB + 1) / 2];
+#pragma unroll
+    for (int w = 0; w < (NQB + 1) / 2; ++w) text_bits[w] = 0u;
+#pragma unroll
+    for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (wq[mb * 32 + acc_row(v, half)] == 0) text_bits[mb / 2] |= 1u << ((mb & 1) * 16 + v);
+
+    const int cpw = p.chunk_keys / kWaves;
+    const int jb = c0 + wave * cpw;
+    const int je = min(jb + cpw, L);
+    const int ntiles = je > jb ? (je - jb + kTile - 1) / kTile : 0;
+    const int rank_end = L - R;                                   // keys >= rank_end are not ranked
+    const int mask_from = min(rank_end, p.causal ? L - O : L);    // below: no masking needed
+    const int64_t tok_bytes = p.k_stride_tok * G::EB;
+
+    for (int g = 0; g < p.sel_group; ++g) {
+        const int hq = sg * p.sel_group + g;
+        const int hk = hq / p.G;
+        __syncthreads();  // previous head's nlse_s / q_lds are no longer read
+        if (tid < NQB * 32) {
+            float nl = NEG_INF;
+            if (tid < O) {
+                const float2* part = reinterpret_cast<const float2*>(p.part) + ((size_t)(b * p.H_q + hq) * p.n_chunks) * O + tid;
+                float M = NEG_INF;
+                for (int ch = 0; ch < n_chunks_b; ++ch) M = fmaxf(M, part[(size_t)ch * O].x);
+                float Ls = 0.f;
+                for (int ch = 0; ch < n_chunks_b; ++ch) {
+                    const float2 r = part[(size_t)ch * O];
+                    Ls += r.y * fast_exp2(r.x - M);
+                }
+                Ls += p.n_score * fast_exp2(-M);  // the n of the n-softmax, in the same scaled units
+                nl = -(M + fast_log2(Ls));
+            }
+            nlse_s[tid] = nl;
+        }
+        QFrags<E, D, NQB> qf;
+        qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
+        __syncthreads();
+        float nl[NQB][16];
+#pragma unroll
+        for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) nl[mb][v] = nlse_s[mb * 32 + acc_row(v, half)];
+
+        const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
+        u32x4 st[G::NLD];
+        if (ntiles > 0) load_tile<E, D>(st, kbase, tok_bytes, jb, L, lane);
+        for (int t = 0; t < ntiles; ++t) {
+            const int j0 = jb + t * kTile;
+            wave_lds_sync();
+            store_tile<E, D>(st, tile, lane);
+            wave_lds_sync();
+            if (t + 1 < ntiles) load_tile<E, D>(st, kbase, tok_bytes, j0 + kTile, L, lane);
+
+            f32x16 acc[NQB];
+#pragma unroll
+            for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < G::NK; ++s) {
+                const auto kf = k_frag<E, D>(tile, s, lane);
+#pragma unroll
+                for (int mb = 0; mb < NQB; ++mb) acc[mb] = mma(qf.get(mb, s, lane, q_lds), kf, acc[mb]);
+            }
+            // acc[mb][v]: query mb*32 + acc_row(v, half), key j0 + lane%32
+            const int j = j0 + (lane & 31);
+            const bool need_mask = j0 + kTile > mask_from;
+            float ct = 0.f, cv = 0.f;  // sums over text / visual window rows
+#pragma unroll
+            for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    float pv = fast_exp2(fmaf(acc[mb][v], c, nl[mb][v]));
+                    if (need_mask) {
+                        const int i = mb * 32 + acc_row(v, half);
+                        const bool ok = j < rank_end && (!p.causal || j <= L - O + i);
+                        pv = ok ? pv : 0.f;
+                    }
+                    if (mixed) {
+                        const bool is_text = (text_bits[mb / 2] >> ((mb & 1) * 16 + v)) & 1u;
+                        ct += is_text ? pv : 0.f;
+                        cv += is_text ? 0.f : pv;
+                    } else {
+                        ct += pv;
+                    }
+                }
+            ct += __shfl_xor(ct, 32);
+            if (mixed) cv += __shfl_xor(cv, 32);
+            else if (any_vis) { cv = ct; ct = 0.f; }  // an all-visual window: every row is a visual query
+            if (half == 0 && j < L) {
+                const bool key_text = p.modality[seq0 + j] == 0;
+                float s_self = key_text ? ct : cv;
+                float s_cross = key_text ? cv : ct;
+                const size_t o = (size_t)sg * p.total_tokens + seq0 + j;
+                if (g > 0) {  // same thread wrote these in the previous head iteration
+                    s_self += p.score_self[o];
+                    s_cross += p.score_cross[o];
+                }
+                p.score_self[o] = s_self;
+                p.score_cross[o] = s_cross;
+            }
+        }
+    }
+}
+
+template <typename E, int D, int NQB>
+hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
+    using SM = Smem<E, D, NQB>;
+    const size_t smem = SM::total;
+    auto ka = score_stats_kernel<E, D, NQB>;
+    auto kb = score_colsum_kernel<E, D, NQB>;
+    if (smem > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ka), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kb), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    const dim3 block(kThreads);
+    const dim3 grid_a(p.n_chunks, p.H_q, p.B);
+    const dim3 grid_b(p.n_chunks, p.H_q / p.sel_group, p.B);
+    hipLaunchKernelGGL(ka, grid_a, block, smem, s, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kb, grid_b, block, smem, s, p);
+    return hipGetLastError();
+}
+
+template <typename E, int D>
+hipError_t launch_nqb(const ScoreParams& p, hipStream_t s) {
+    if (p.O <= 32) return launch_typed<E, D, 1>(p, s);
+    if (p.O <= 64) return launch_typed<E, D, 2>(p, s);
+    return launch_typed<E, D, 4>(p, s);
+}
+
+}  // namespace
+
+int score_chunk_keys(int B, int H_q, int max_seqlen) {
+    int ck = 2048;
+    while (ck > 128 && (int64_t)B * H_q * ((max_seqlen + ck - 1) / ck) < 2048) ck >>= 1;
+    return ck;
+}
+
+hipError_t launch_score(const ScoreParams& p, int dtype, int D, int /*max_seqlen*/, hipStream_t s) {
+    if (dtype == CSP_BF16) return D == 128 ? launch_nqb<bf16_tag, 128>(p, s) : launch_nqb<bf16_tag, 64>(p, s);
+    return D == 128 ? launch_nqb<f32_tag, 128>(p, s) : launch_nqb<f32_tag, 64>(p, s);
+}
+
+}  // namespace csp
