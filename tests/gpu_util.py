@@ -41,6 +41,9 @@ class DeviceCase:
 def assert_scores_close(gpu: np.ndarray, ref: np.ndarray, what: str = "") -> None:
     ref = np.asarray(ref, np.float64)
     gpu = np.asarray(gpu, np.float64)
+    assert gpu.shape == ref.shape, f"{what}: shape {gpu.shape} vs {ref.shape}"
+    if ref.size == 0:
+        return
     tol = REL * np.abs(ref) + ABS_FLOOR * np.abs(ref).max()
     bad = np.abs(gpu - ref) > tol
     if bad.any():
