@@ -1,0 +1,300 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSP hot path on one MI355X.
+
+A step is one pass of the whole path over the 7B-shape 16k-token batch
+(32 layers x batch 4 x 32 heads x 16384 tokens, head_dim 128, bf16, window 64):
+per layer score -> select -> compact at the given budget, then the decode loop
+(append + n-softmax attention over the pruned cache) for every layer and every
+decode step.  Inputs are synthetic, seeded, and resident in HBM before the timed
+region starts.
+
+Prints ONE JSON line: `value` is pruned KV tokens per second over
+score+select+compact (layers x tokens / time of the pruning phase); the decode
+attention bandwidth, the roofline of the dominant kernel and the CPU-oracle
+baseline ride along in the same object.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+WORKLOADS = {
+    # name: (layers, B, H, D, L, window, images, vis_per_image, text, decode_steps)
+    "7b_16k": dict(layers=32, B=4, H=32, D=128, L=16384, O=64, images=20, vis=576, text=4864, steps=128),
+    "7b_4k": dict(layers=1, B=1, H=32, D=128, L=4096, O=64, images=4, vis=576, text=1792, steps=16),
+}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="7b_16k", choices=list(WORKLOADS))
+    ap.add_argument("--budget", type=float, default=0.5, help="cache budget as a fraction of the sequence length")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
+    ap.add_argument("--decode-steps", type=int, default=-1, help="override the decode steps per pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-second-budget", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def build_inputs(cfg, n_layers, device):
+    import numpy as np
+    import csp_workloads as W
+    layers = []
+    for l in range(n_layers):
+        rng = np.random.default_rng(1000 + l)
+        if cfg["L"] == 4096:
+            layouts = [W.layout_7b_4k() for _ in range(cfg["B"])]
+        else:
+            layouts = [W.layout_random(rng, [cfg["vis"]] * cfg["images"], cfg["text"], cfg["O"]) for _ in range(cfg["B"])]
+        q, k, v, mod, cu_dev, cu = W.device_qkv(layouts, H_q=cfg["H"], H_kv=cfg["H"], D=cfg["D"], O=cfg["O"],
+                                                seed=l, device=device)
+        layers.append(dict(q=q, k=k, v=v, mod=mod, cu=cu.tolist(), layouts=layouts))
+    return layers
+
+
+def make_layers(cfg, inputs, budget_frac, decode_steps, device):
+    from paper_2412_04652_amd.runner import CspLayer
+    T = int(cfg["L"] * budget_frac)
+    return [CspLayer(dtype="bf16", H_q=cfg["H"], H_kv=cfg["H"], D=cfg["D"], O=cfg["O"], R=cfg["O"],
+                     cu_seqlens=inp["cu"], budgets=[T] * cfg["B"], decode_cap=decode_steps, device=device)
+            for inp in inputs], T
+
+
+class Timer:
+    """HIP events on torch's current stream (the stream every kernel here is launched on)."""
+
+    def __init__(self):
+        import torch
+        self.torch = torch
+        self.pairs = {}
+
+    def span(self, name):
+        t = self.torch
+        a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        self.pairs.setdefault(name, []).append((a, b))
+        return a, b
+
+    def totals_ms(self):
+        return {k: [a.elapsed_time(b) for a, b in v] for k, v in self.pairs.items()}
+
+
+def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8):
+    """One step: prune every layer, then the decode loop.  Event pairs bracket the
+    phases; every `sample_every`-th call of each kernel family is bracketed on its own."""
+    n_call = 0
+    a, b = timer.span("prune")
+    a.record()
+    for inp, lay in zip(inputs, layers):
+        sampled = (n_call % sample_every) == 0
+        n_call += 1
+        if sampled:
+            e0, e1 = timer.span("score"); e0.record()
+        lay.score(inp["q"], inp["k"], inp["mod"])
+        if sampled:
+            e1.record(); e2, e3 = timer.span("select"); e2.record()
+        lay.select(inp["mod"])
+        if sampled:
+            e3.record(); e4, e5 = timer.span("compact"); e4.record()
+        lay.compact(inp["k"], inp["v"])
+        if sampled:
+            e5.record()
+    b.record()
+    a, b = timer.span("decode")
+    a.record()
+    n_call = 0
+    for t in range(decode_steps):
+        for li, lay in enumerate(layers):
+            lay.append(dec["k"][t % dec["n"]], dec["v"][t % dec["n"]])
+            sampled = (n_call % sample_every) == 0
+            n_call += 1
+            if sampled:
+                e0, e1 = timer.span("decode_call"); e0.record()
+            lay.decode(dec["q"][t % dec["n"]])
+            if sampled:
+                e1.record()
+    b.record()
+
+
+def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device):
+    import torch
+    layers, T = make_layers(cfg, inputs, budget_frac, decode_steps, device)
+    g = torch.Generator(device=device); g.manual_seed(777)
+    nd = 4
+    dec = dict(n=nd,
+               q=[torch.randn((cfg["B"], cfg["H"], cfg["D"]), generator=g, device=device).to(torch.bfloat16) for _ in range(nd)],
+               k=[torch.randn((cfg["B"], cfg["H"], cfg["D"]), generator=g, device=device).to(torch.bfloat16) for _ in range(nd)],
+               v=[torch.randn((cfg["B"], cfg["H"], cfg["D"]), generator=g, device=device).to(torch.bfloat16) for _ in range(nd)])
+    for _ in range(warmup):
+        run_pass(cfg, inputs, layers, dec, decode_steps, Timer())
+    torch.cuda.synchronize()
+    timer = Timer()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run_pass(cfg, inputs, layers, dec, decode_steps, timer)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = timer.totals_ms()
+    n_layers, B, H, D, L, O = len(layers), cfg["B"], cfg["H"], cfg["D"], cfg["L"], cfg["O"]
+    e = 2
+    avg = lambda xs: sum(xs) / max(len(xs), 1)
+    # algorithmic bytes per launch (one layer)
+    by_score = B * (H * L * D * e + H * O * D * e + L + 2 * H * (L - O) * 4)
+    by_select = B * (2 * H * (L - O) * 4 + H * T * 4)
+    by_compact = B * (4 * H * T * D * e + H * T * 4)
+    kv_mean = T + (decode_steps + 1) / 2.0
+    by_decode = B * (2 * H * kv_mean * D * e + H * D * (e + 4))
+    prune_ms = avg(ms["prune"])
+    res = dict(
+        budget=budget_frac, T=T, layers=n_layers,
+        prune_ms=prune_ms,
+        tokens_per_s=n_layers * B * L / (prune_ms * 1e-3),
+        prune_gbps=n_layers * (by_score + by_select + by_compact) / (prune_ms * 1e-3) / 1e9,
+        ms_per_step=wall / steps * 1e3,
+        kernels={
+            "score(2 kernels)": dict(ms=avg(ms["score"]), gbps=by_score / (avg(ms["score"]) * 1e-3) / 1e9, bytes=by_score),
+            "select": dict(ms=avg(ms["select"]), gbps=by_select / (avg(ms["select"]) * 1e-3) / 1e9, bytes=by_select),
+            "compact": dict(ms=avg(ms["compact"]), gbps=by_compact / (avg(ms["compact"]) * 1e-3) / 1e9, bytes=by_compact),
+        })
+    if decode_steps > 0:
+        dec_ms = avg(ms["decode"])
+        call_ms = avg(ms["decode_call"])
+        res.update(decode_ms_per_token=dec_ms / decode_steps,
+                   decode_gbps=by_decode * n_layers * decode_steps / (dec_ms * 1e-3) / 1e9)
+        res["kernels"]["decode_attn(split+merge)"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
+    del layers
+    torch.cuda.empty_cache()
+    return res
+
+
+def copy_peak(device):
+    """Plain device-to-device copy of 2 GiB: the achievable stream bandwidth on this machine."""
+    import torch
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.int16, device=device).fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    return 10 * 2 * n * 2 / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
+def cpu_baseline(cfg, inputs, budget_frac, target_s):
+    """The CPU oracle, as it stands, on a bounded sample of (sequence, head) problems of layer 0:
+    score -> select -> gather -> one decode step each."""
+    import numpy as np
+    from oracle import csp_oracle as orc
+    L, O, D, H = cfg["L"], cfg["O"], cfg["D"], cfg["H"]
+    T = int(L * budget_frac)
+    inp = inputs[0]
+    threads = orc.max_threads()
+
+    def fetch_range(start, n):
+        qs, ks, vs, ms = [], [], [], []
+        for p in range(start, start + n):
+            b, h = divmod(p, H)
+            b %= cfg["B"]
+            lo = inp["cu"][b]
+            qs.append(inp["q"][b, h].float().cpu().numpy().astype(np.float64))
+            ks.append(inp["k"][h, lo:lo + L].float().cpu().numpy().astype(np.float64))
+            vs.append(inp["v"][h, lo:lo + L].float().cpu().numpy().astype(np.float64))
+            ms.append(inp["mod"][lo:lo + L].cpu().numpy())
+        return np.stack(qs), np.stack(ks), np.stack(vs), np.stack(ms)
+
+    def run(q, k, v, m):
+        t0 = time.perf_counter()
+        a_s, a_c = orc.scores_batch(q, k, m, O, 0.0, True)
+        dq = np.ones((q.shape[0], D))
+        kc, vc = [], []
+        for p in range(q.shape[0]):
+            idx, _ = orc.select(a_s[p], a_c[p], m[p], O, O, T, 0.5)
+            kc.append(orc.gather(k[p], idx)); vc.append(orc.gather(v[p], idx))
+        orc.decode_batch(dq, np.stack(kc), np.stack(vc), 1.0)
+        return time.perf_counter() - t0
+
+    # batches of 4 problems per thread (different heads each time) until the time target is met
+    per_batch, n, t1, start = 4 * threads, 0, 0.0, 0
+    while t1 < target_s and n < 64 * threads:
+        q, k, v, m = fetch_range(start, per_batch)
+        t1 += run(q, k, v, m)
+        n += per_batch
+        start += per_batch
+    seq_layers = n / H                             # one (layer, sequence) needs all H heads
+    return dict(value=seq_layers * L / t1, unit="tokens/s", cores=threads, kind="oracle",
+                sample=f"{n} (sequence, head) problems of layer 0 at L={L}: score+select+gather and one decode step each, "
+                       f"{t1:.1f} s of wall time on {threads} OpenMP threads, scaled linearly (heads are independent)")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2412_04652_amd as pkg
+    pkg.load_library()                              # no fallback: the HIP library must be there
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    device = torch.device("cuda:0")
+    cfg = WORKLOADS[args.workload]
+    n_layers = args.layers or cfg["layers"]
+    decode_steps = cfg["steps"] if args.decode_steps < 0 else args.decode_steps
+    inputs = build_inputs(cfg, n_layers, device)
+    torch.cuda.synchronize()
+    main_res = measure(cfg, inputs, args.budget, decode_steps, args.steps, args.warmup, device)
+    second = None
+    if not args.no_second_budget and args.workload == "7b_16k":
+        second = measure(cfg, inputs, 0.2 if abs(args.budget - 0.5) < 1e-9 else 0.5, decode_steps, 1, 1, device)
+    peak_copy = copy_peak(device)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds)
+
+    # dominant kernel of the step by time
+    kern = main_res["kernels"]
+    step_share = {k: v["ms"] * (n_layers * (decode_steps if k.startswith("decode") else 1)) for k, v in kern.items()}
+    dom = max(step_share, key=step_share.get)
+    roof = dict(bound="hbm", kernel=dom, achieved=kern[dom]["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s",
+                frac=kern[dom]["gbps"] / HBM_PEAK_GBPS, traffic=None,
+                algorithmic_bytes_per_launch=kern[dom]["bytes"], avg_launch_ms=kern[dom]["ms"])
+    out = {
+        "metric": "pruned KV tokens/sec (score+select+compact) and decode attn HBM GB/s, 1 GPU",
+        "value": main_res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {n_layers} layers x B{cfg['B']} x H{cfg['H']} x L{cfg['L']} x D{cfg['D']} bf16, "
+                               f"window {cfg['O']}, budget {args.budget:g}, {decode_steps} decode steps",
+                   "budget": args.budget, "layers": n_layers, "decode_steps": decode_steps},
+        "prune_ms_all_layers": main_res["prune_ms"],
+        "prune_hbm_gbps": main_res["prune_gbps"], "prune_frac_of_peak": main_res["prune_gbps"] / HBM_PEAK_GBPS,
+        "decode_attn_hbm_gbps": main_res.get("decode_gbps"),
+        "decode_frac_of_peak": (main_res.get("decode_gbps") or 0.0) / HBM_PEAK_GBPS,
+        "decode_ms_per_token_all_layers": main_res.get("decode_ms_per_token"),
+        "copy_peak_gbps": peak_copy,
+        "kernels": kern,
+        "roofline": roof,
+        "cpu_baseline": cpu,
+    }
+    if second is not None:
+        out["second_budget"] = {k: second[k] for k in ("budget", "T", "prune_ms", "tokens_per_s", "prune_gbps",
+                                                       "decode_gbps", "decode_ms_per_token") if k in second}
+        out["second_budget"]["kernels"] = second["kernels"]
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
