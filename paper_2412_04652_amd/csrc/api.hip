@@ -144,7 +144,7 @@ int csp_select(const csp_desc* d, const float* score_self, const float* score_cr
     p.B = d->B; p.H_sel = c.H_sel; p.O = d->window_O; p.R = d->recent_R; p.kept_cap = kept_cap;
     p.total_tokens = c.total_tokens;
     p.cross_ratio = d->cross_ratio;
-    return launch_select(p, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+    return launch_select(p, d->max_seqlen, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
 }
 
 int csp_compact(const csp_desc* d, const void* k, const void* v, const int32_t* kept_idx,

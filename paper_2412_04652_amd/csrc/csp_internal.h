@@ -98,7 +98,7 @@ struct DecodeParams {
 
 // ---- launchers (one per kernel family; each returns a hipError_t) -----------
 hipError_t launch_score(const ScoreParams& p, int dtype, int D, int max_seqlen, hipStream_t s);
-hipError_t launch_select(const SelectParams& p, hipStream_t s);
+hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s);
 hipError_t launch_compact(const CompactParams& p, int row_bytes, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_decode(const DecodeParams& p, int dtype, int D, hipStream_t s);

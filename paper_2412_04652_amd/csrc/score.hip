@@ -339,19 +339,13 @@ __global__ __launch_bounds__(kThreads) void score_colsum_kernel(ScoreParams p) {
                     Ls += r.y * fast_exp2(r.x - M);
                 }
                 Ls += p.n_score * fast_exp2(-M);  // the n of the n-softmax, in the same scaled units
-                nl = -(M + fast_log2(Ls));
+                nl = -(M + fast_log2(Ls)) / c;  // in units of the raw dot product: seeds the accumulator
             }
             nlse_s[tid] = nl;
         }
         QFrags<E, D, NQB> qf;
         qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
         __syncthreads();
-        float nl[NQB][16];
-#pragma unroll
-        for (int mb = 0; mb < NQB; ++mb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) nl[mb][v] = nlse_s[mb * 32 + acc_row(v, half)];
-
         const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
         u32x4 st[G::NLD];
         if (ntiles > 0) load_tile<E, D>(st, kbase, tok_bytes, jb, L, lane);
@@ -362,11 +356,16 @@ __global__ __launch_bounds__(kThreads) void score_colsum_kernel(ScoreParams p) {
             wave_lds_sync();
             if (t + 1 < ntiles) load_tile<E, D>(st, kbase, tok_bytes, j0 + kTile, L, lane);
 
+            // the accumulator starts at -lse_i/c, so that 2^(c*acc) is the normalised weight
             f32x16 acc[NQB];
 #pragma unroll
             for (int mb = 0; mb < NQB; ++mb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const float4 w = *reinterpret_cast<const float4*>(nlse_s + mb * 32 + v4 * 8 + half * 4);
+                    acc[mb][v4 * 4 + 0] = w.x; acc[mb][v4 * 4 + 1] = w.y;
+                    acc[mb][v4 * 4 + 2] = w.z; acc[mb][v4 * 4 + 3] = w.w;
+                }
 #pragma unroll
             for (int s = 0; s < G::NK; ++s) {
                 const auto kf = k_frag<E, D>(tile, s, lane);
@@ -381,7 +380,7 @@ __global__ __launch_bounds__(kThreads) void score_colsum_kernel(ScoreParams p) {
             for (int mb = 0; mb < NQB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float pv = fast_exp2(fmaf(acc[mb][v], c, nl[mb][v]));
+                    float pv = fast_exp2(acc[mb][v] * c);
                     if (need_mask) {
                         const int i = mb * 32 + acc_row(v, half);
                         const bool ok = j < rank_end && (!p.causal || j <= L - O + i);

@@ -9,11 +9,15 @@
 // are non-negative floats, so their bit patterns order like unsigned integers:
 // an MSB-first radix select (11 + 11 + 10 bits, LDS histograms for both
 // regions at once) finds, per region, the bit pattern of the K-th largest score
-// and how many keys equal to it still fit.  A final ordered sweep turns
-// "greater than the threshold, or equal and among the first few equals" into
-// keep flags and scatters the kept positions with a ballot/popcount prefix
-// scan, which yields ascending indices and the lower-index-first tie rule
-// without atomics on the output.
+// and how many keys equal to it still fit.  Each wavefront owns a contiguous
+// run of ITEMS*64 keys of a super-block of 1024*ITEMS keys and reads it with
+// coalesced loads (lane l holds keys l, l+64, ...), so "greater than the
+// threshold, or equal and among the first few equals" is a chain of wave
+// ballots and popcounts in key order plus two block-wide exchanges of
+// per-wavefront totals per super-block; the kept positions come out ascending,
+// with the lower-index-first tie rule, and without atomics on the output.  With a single-modality window every key belongs to exactly one
+// region: one bit pattern per key stays in registers for all passes when the
+// sequence fits one super-block.
 #include "csp_internal.h"
 
 namespace csp {
@@ -22,14 +26,24 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kBins = 2048;
+constexpr uint32_t kNone = 0xffffffffu;  // "not a candidate": no finite non-negative float
 
-struct Thresh {
-    uint32_t bits;   // bit pattern of the K-th largest score of the region
-    uint32_t n_eq;   // how many keys equal to it are kept (lowest indices first)
+#ifdef CSP_SEL_TRACE
+__device__ long long g_sel_trace[32];
+#define SEL_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) g_sel_trace[k] = wall_clock64(); } while (0)
+#else
+#define SEL_STAMP(k) do {} while (0)
+#endif
+
+struct SelShared {
+    uint32_t hist[2][kBins];
+    uint64_t wsum[kSelWaves];
+    uint32_t has[2];
+    uint32_t digit[2], rem[2];
 };
 
 // Exclusive prefix (over threads, in thread order) and grand total of a packed
-// pair of 32-bit counters.  wsum: kSelWaves entries of scratch LDS.
+// pair of 32-bit counters.
 __device__ __forceinline__ void block_scan_pair(uint64_t v, uint64_t* wsum, uint64_t& excl, uint64_t& total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     uint64_t inc = v;
@@ -52,38 +66,70 @@ __device__ __forceinline__ void block_scan_pair(uint64_t v, uint64_t* wsum, uint
     __syncthreads();  // wsum may be reused
 }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
-    __shared__ uint32_t hist[2][kBins];
-    __shared__ uint64_t wsum[kSelWaves];
-    __shared__ uint32_t wcnt[3][kSelWaves];
-    __shared__ uint32_t sh_has[2];
-    __shared__ uint32_t sh_digit[2], sh_rem[2];
+struct SelCtx {
+    const uint8_t* mod;
+    const float* sc_self;
+    const float* sc_cross;
+    int32_t* out;
+    int32_t* cnt;
+    int L, P, T, R, kept_cap;
+    bool has0, has1;
+    double cross_ratio;
+};
 
-    const int sg = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seq0 = p.cu[b];
-    const int L = p.cu[b + 1] - seq0;
-    const int T = p.budget_T[b];
-    const int R = p.R, O = p.O;
-    int32_t* out = p.kept_idx + ((size_t)b * p.H_sel + sg) * p.kept_cap;
-    int32_t* cnt = p.kept_cnt + ((size_t)b * p.H_sel + sg) * 4;
+// ITEMS consecutive keys per thread and super-block.  DUAL: the window holds both
+// modalities, every prefix key is a candidate of both regions (two bit patterns per
+// key); otherwise one pattern plus a region bit.  CACHED: the sequence fits one
+// super-block and the patterns are loaded once.
+template <int ITEMS, bool DUAL, bool CACHED>
+__device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
+    const int tid = threadIdx.x;
+    constexpr int SUPER = kSelThreads * ITEMS;
+    const int n_super = CACHED ? 1 : (c.L + SUPER - 1) / SUPER;
 
-    if (L <= T) {  // the cache already fits the budget: keep everything
-        for (int j = tid; j < p.kept_cap; j += kSelThreads) out[j] = j < L ? j : -1;
-        if (tid == 0) { cnt[0] = L; cnt[1] = 0; cnt[2] = 0; cnt[3] = 0; }
-        return;
-    }
+    uint32_t ka[ITEMS];                 // self-region pattern, or the key's only pattern
+    uint32_t kb[DUAL ? ITEMS : 1];      // cross-region pattern (DUAL only)
+    uint32_t in_cross = 0u;             // !DUAL: bit i set = key i ranks in the cross region
 
-    const int P = L - R;  // rankable prefix
-    const uint8_t* mod = p.modality + seq0;
-    const float* sc_self = p.score_self + (size_t)sg * p.total_tokens + seq0;
-    const float* sc_cross = p.score_cross + (size_t)sg * p.total_tokens + seq0;
+    const int lane = tid & 63, wave = tid >> 6;
+    // key i of this lane in super-block sb
+    auto key_index = [&](int sb, int i) { return sb * SUPER + wave * (ITEMS * kWave) + i * kWave + lane; };
+    auto load_keys = [&](int sb) {
+        uint8_t m[ITEMS];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int j = key_index(sb, i);
+            m[i] = j < c.P ? c.mod[j] : 0;
+        }
+        in_cross = 0u;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int j = key_index(sb, i);
+            if constexpr (DUAL) {
+                ka[i] = j < c.P ? __float_as_uint(c.sc_self[j]) : kNone;
+                kb[i] = j < c.P ? __float_as_uint(c.sc_cross[j]) : kNone;
+            } else {
+                // the window has one modality: keys sharing it rank in the self region, the rest in cross
+                const bool self_key = m[i] ? c.has1 : c.has0;
+                ka[i] = kNone;
+                if (j < c.P) ka[i] = __float_as_uint(self_key ? c.sc_self[j] : c.sc_cross[j]);
+                if (!self_key) in_cross |= 1u << i;
+            }
+        }
+    };
+    // region r pattern of key i (kNone if key i is not a candidate of region r)
+    auto pat = [&](int i, int r) -> uint32_t {
+        if constexpr (DUAL) {
+            return r == 0 ? ka[i] : kb[i];
+        } else {
+            const bool cr = (in_cross >> i) & 1u;
+            return (cr == (r == 1)) ? ka[i] : kNone;
+        }
+    };
 
-    if (tid < 2) sh_has[tid] = 0;
-    __syncthreads();
-    for (int i = tid; i < O; i += kSelThreads) atomicOr(&sh_has[mod[L - O + i] ? 1 : 0], 1u);
-    __syncthreads();
-    const bool has0 = sh_has[0] != 0, has1 = sh_has[1] != 0;
+    SEL_STAMP(1);
+    if (CACHED) load_keys(0);
+    SEL_STAMP(2);
 
     // ---- radix select, both regions at once ---------------------------------
     uint32_t prefix[2] = {0u, 0u};   // threshold bits found so far (high part)
@@ -96,35 +142,45 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
         const int nbits = pass == 2 ? 10 : 11;
         const int prev_shift = pass == 1 ? 21 : 10;  // bits above the current digit
         const uint32_t dmask = (1u << nbits) - 1u;
-        for (int i = tid; i < 2 * kBins; i += kSelThreads) (&hist[0][0])[i] = 0u;
+        SEL_STAMP(3 + pass * 4);
+        for (int i = tid; i < 2 * kBins; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
         __syncthreads();
-        for (int j = tid; j < P; j += kSelThreads) {
-            const int mj = mod[j] ? 1 : 0;
-            const bool in_s = mj ? has1 : has0;   // some window query shares the key's modality
-            const bool in_c = mj ? has0 : has1;   // some window query has the other modality
-            if (in_s && !none[0]) {
-                const uint32_t bits = __float_as_uint(sc_self[j]);
-                if (pass == 0 || (bits >> prev_shift) == prefix[0]) atomicAdd(&hist[0][(bits >> shift) & dmask], 1u);
-            }
-            if (in_c && !none[1]) {
-                const uint32_t bits = __float_as_uint(sc_cross[j]);
-                if (pass == 0 || (bits >> prev_shift) == prefix[1]) atomicAdd(&hist[1][(bits >> shift) & dmask], 1u);
+        SEL_STAMP(4 + pass * 4);
+#pragma unroll 1
+        for (int sb = 0; sb < n_super; ++sb) {
+            if (!CACHED) load_keys(sb);
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                if constexpr (DUAL) {
+#pragma unroll
+                    for (int r = 0; r < 2; ++r) {
+                        const uint32_t a = pat(i, r);
+                        if (a != kNone && !none[r] && (pass == 0 || (a >> prev_shift) == prefix[r]))
+                            atomicAdd(&sh.hist[r][(a >> shift) & dmask], 1u);
+                    }
+                } else {
+                    const int r = (in_cross >> i) & 1u;  // the key's only region
+                    const uint32_t a = ka[i];
+                    if (a != kNone && !(r ? none[1] : none[0]) && (pass == 0 || (a >> prev_shift) == (r ? prefix[1] : prefix[0])))
+                        atomicAdd(&sh.hist[r][(a >> shift) & dmask], 1u);
+                }
             }
         }
         __syncthreads();
+        SEL_STAMP(5 + pass * 4);
         // thread t owns bins hi = nb-1-2t and lo = hi-1 (descending order over threads)
         const int nb = 1 << nbits;
         const int hi = nb - 1 - 2 * tid;
         uint32_t c_hi[2] = {0u, 0u}, c_lo[2] = {0u, 0u};
-        if (hi >= 0) { c_hi[0] = hist[0][hi]; c_hi[1] = hist[1][hi]; }
-        if (hi >= 1) { c_lo[0] = hist[0][hi - 1]; c_lo[1] = hist[1][hi - 1]; }
+        if (hi >= 0) { c_hi[0] = sh.hist[0][hi]; c_hi[1] = sh.hist[1][hi]; }
+        if (hi >= 1) { c_lo[0] = sh.hist[0][hi - 1]; c_lo[1] = sh.hist[1][hi - 1]; }
         uint64_t excl, total;
-        block_scan_pair((uint64_t)(c_hi[0] + c_lo[0]) | ((uint64_t)(c_hi[1] + c_lo[1]) << 32), wsum, excl, total);
+        block_scan_pair((uint64_t)(c_hi[0] + c_lo[0]) | ((uint64_t)(c_hi[1] + c_lo[1]) << 32), sh.wsum, excl, total);
         if (pass == 0) {
             // budget rule: K_sel = T - R split by cross_ratio, excess of a short side spills over
             const int n_s = (int)(uint32_t)total, n_c = (int)(uint32_t)(total >> 32);
-            const int K_sel = T - R;
-            int kc = (int)floor(p.cross_ratio * (double)K_sel);
+            const int K_sel = c.T - c.R;
+            int kc = (int)floor(c.cross_ratio * (double)K_sel);
             kc = kc > K_sel ? K_sel : (kc < 0 ? 0 : kc);
             int ks = K_sel - kc;
             if (ks > n_s) { kc += ks - n_s; ks = n_s; }
@@ -139,91 +195,157 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
             if (none[r]) continue;
             const uint32_t e = (uint32_t)(excl >> (32 * r));
             const uint32_t K = k_rem[r];
-            if (hi >= 0 && e < K && K <= e + c_hi[r]) { sh_digit[r] = (uint32_t)hi; sh_rem[r] = K - e; }
-            else if (hi >= 1 && e + c_hi[r] < K && K <= e + c_hi[r] + c_lo[r]) { sh_digit[r] = (uint32_t)(hi - 1); sh_rem[r] = K - e - c_hi[r]; }
+            if (hi >= 0 && e < K && K <= e + c_hi[r]) { sh.digit[r] = (uint32_t)hi; sh.rem[r] = K - e; }
+            else if (hi >= 1 && e + c_hi[r] < K && K <= e + c_hi[r] + c_lo[r]) { sh.digit[r] = (uint32_t)(hi - 1); sh.rem[r] = K - e - c_hi[r]; }
         }
         __syncthreads();
 #pragma unroll
         for (int r = 0; r < 2; ++r) {
             if (none[r]) continue;
-            prefix[r] = (prefix[r] << nbits) | sh_digit[r];
-            k_rem[r] = sh_rem[r];
+            prefix[r] = (prefix[r] << nbits) | sh.digit[r];
+            k_rem[r] = sh.rem[r];
         }
         __syncthreads();
     }
-    Thresh th[2];
+    SEL_STAMP(15);
+    uint32_t th_bits[2], th_eq[2];  // K-th largest pattern of the region; equals still to keep
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-        th[r].bits = none[r] ? 0xffffffffu : prefix[r];  // no finite non-negative float has this pattern
-        th[r].n_eq = none[r] ? 0u : k_rem[r];
+        th_bits[r] = none[r] ? 0xfffffffeu : prefix[r];  // above every finite non-negative float: nothing is kept
+        th_eq[r] = none[r] ? 0u : k_rem[r];
     }
 
-    // ---- ordered sweep: flags -> ranks -> scatter ----------------------------
-    uint32_t base_eq[2] = {0u, 0u};  // equals of each region seen in earlier blocks
+    // ---- ordered sweep: equal ranks, keep flags, positions --------------------
+    uint32_t base_eq[2] = {0u, 0u};  // equals of each region in earlier super-blocks
     uint32_t base_out = 0u, n_both = 0u;
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    for (int j0 = 0; j0 < L; j0 += kSelThreads) {
-        const int j = j0 + tid;
-        bool gt[2] = {false, false}, eq[2] = {false, false};
-        const bool tail = j >= P && j < L;
-        if (j < P) {
-            const int mj = mod[j] ? 1 : 0;
-            const bool in_s = mj ? has1 : has0;
-            const bool in_c = mj ? has0 : has1;
-            if (in_s) { const uint32_t bits = __float_as_uint(sc_self[j]); gt[0] = bits > th[0].bits; eq[0] = bits == th[0].bits; }
-            if (in_c) { const uint32_t bits = __float_as_uint(sc_cross[j]); gt[1] = bits > th[1].bits; eq[1] = bits == th[1].bits; }
-        }
-        const uint64_t b0 = __ballot(eq[0]), b1 = __ballot(eq[1]);
-        if (lane == 0) { wcnt[0][wave] = __popcll(b0); wcnt[1][wave] = __popcll(b1); }
+    uint64_t* wtot = sh.wsum;
+    // exclusive prefix over wavefronts and grand total of a packed pair of per-wavefront counters
+    auto wave_exchange = [&](uint64_t mine, uint64_t& before, uint64_t& all) {
+        if (lane == 0) wtot[wave] = mine;
         __syncthreads();
-        uint32_t before0 = 0, before1 = 0, tot0 = 0, tot1 = 0;
+        before = 0; all = 0;
 #pragma unroll
         for (int w = 0; w < kSelWaves; ++w) {
-            const uint32_t a = wcnt[0][w], c = wcnt[1][w];
-            if (w < wave) { before0 += a; before1 += c; }
-            tot0 += a; tot1 += c;
+            const uint64_t v = wtot[w];
+            if (w < wave) before += v;
+            all += v;
         }
-        const uint32_t rank0 = base_eq[0] + before0 + __popcll(b0 & lt_mask);
-        const uint32_t rank1 = base_eq[1] + before1 + __popcll(b1 & lt_mask);
-        base_eq[0] += tot0; base_eq[1] += tot1;
-        const bool keep_s = gt[0] || (eq[0] && rank0 < th[0].n_eq);
-        const bool keep_c = gt[1] || (eq[1] && rank1 < th[1].n_eq);
-        const bool keep = keep_s || keep_c || tail;
-        const uint64_t bk = __ballot(keep);
-        const uint64_t bb = __ballot(keep_s && keep_c);
-        if (lane == 0) wcnt[2][wave] = __popcll(bk);
-        n_both += __popcll(bb);  // per-wave partial, reduced at the end
         __syncthreads();
-        uint32_t beforek = 0, totk = 0;
+    };
+#pragma unroll 1
+    for (int sb = 0; sb < n_super; ++sb) {
+        if (!CACHED) load_keys(sb);
+        // 1. equals of each region held by this wavefront
+        uint32_t eqw[2] = {0u, 0u};
+        uint32_t eq_any = 0u;  // bit i: some lane's key i equals a threshold (ties are rare: fast path below)
 #pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) {
-            const uint32_t a = wcnt[2][w];
-            if (w < wave) beforek += a;
-            totk += a;
+        for (int i = 0; i < ITEMS; ++i) {
+            const uint64_t b0 = __ballot(pat(i, 0) == th_bits[0]);
+            const uint64_t b1 = __ballot(pat(i, 1) == th_bits[1]);
+            eqw[0] += __popcll(b0);
+            eqw[1] += __popcll(b1);
+            eq_any |= ((b0 | b1) != 0ull ? 1u : 0u) << i;
         }
-        if (keep) {
-            const uint32_t pos = base_out + beforek + __popcll(bk & lt_mask);
-            if (pos < (uint32_t)p.kept_cap) out[pos] = j;
+        uint64_t before, all;
+        wave_exchange((uint64_t)eqw[0] | ((uint64_t)eqw[1] << 32), before, all);
+        uint32_t run[2] = {base_eq[0] + (uint32_t)before, base_eq[1] + (uint32_t)(before >> 32)};
+        base_eq[0] += (uint32_t)all;
+        base_eq[1] += (uint32_t)(all >> 32);
+        // 2. keep flags in key order (items ascend within the wavefront, lanes within an item)
+        uint32_t keep_bits = 0u, keep_w = 0u, both_w = 0u;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const int j = key_index(sb, i);
+            const uint32_t a0 = pat(i, 0), a1 = pat(i, 1);
+            bool kp0 = a0 != kNone && a0 > th_bits[0];
+            bool kp1 = a1 != kNone && a1 > th_bits[1];
+            if ((eq_any >> i) & 1u) {  // uniform: some key of this item ties with a threshold
+                const bool e0 = a0 == th_bits[0], e1 = a1 == th_bits[1];
+                const uint64_t b0 = __ballot(e0), b1 = __ballot(e1);
+                kp0 = kp0 || (e0 && run[0] + __popcll(b0 & lt_mask) < th_eq[0]);
+                kp1 = kp1 || (e1 && run[1] + __popcll(b1 & lt_mask) < th_eq[1]);
+                run[0] += __popcll(b0);
+                run[1] += __popcll(b1);
+            }
+            const bool keep = kp0 || kp1 || (j >= c.P && j < c.L);   // the last R keys are always kept
+            keep_bits |= (keep ? 1u : 0u) << i;
+            keep_w += __popcll(__ballot(keep));
+            if constexpr (DUAL) both_w += __popcll(__ballot(kp0 && kp1));
         }
-        base_out += totk;
+        wave_exchange((uint64_t)keep_w | ((uint64_t)both_w << 32), before, all);
+        // 3. positions
+        uint32_t pos0 = base_out + (uint32_t)before;
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            const bool keep = (keep_bits >> i) & 1u;
+            const uint64_t bk = __ballot(keep);
+            const uint32_t pos = pos0 + __popcll(bk & lt_mask);
+            if (keep && pos < (uint32_t)c.kept_cap) c.out[pos] = key_index(sb, i);
+            pos0 += __popcll(bk);
+        }
+        base_out += (uint32_t)all;
+        n_both += (uint32_t)(all >> 32);
     }
-    for (int j = (int)base_out + tid; j < p.kept_cap; j += kSelThreads) out[j] = -1;
-    // keys held by both masks: one partial per wavefront
+    SEL_STAMP(16);
+    for (int j = (int)base_out + tid; j < c.kept_cap; j += kSelThreads) c.out[j] = -1;
+    if (tid == 0) { c.cnt[0] = (int32_t)base_out; c.cnt[1] = K_s; c.cnt[2] = K_c; c.cnt[3] = (int32_t)n_both; }
+}
+
+template <int ITEMS>
+__global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
+    __shared__ SelShared sh;
+    SEL_STAMP(0);
+    const int sg = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x;
+    const int seq0 = p.cu[b];
+    SelCtx c;
+    c.L = p.cu[b + 1] - seq0;
+    c.T = p.budget_T[b];
+    c.R = p.R;
+    c.kept_cap = p.kept_cap;
+    c.cross_ratio = p.cross_ratio;
+    c.out = p.kept_idx + ((size_t)b * p.H_sel + sg) * p.kept_cap;
+    c.cnt = p.kept_cnt + ((size_t)b * p.H_sel + sg) * 4;
+
+    if (c.L <= c.T) {  // the cache already fits the budget: keep everything
+        for (int j = tid; j < p.kept_cap; j += kSelThreads) c.out[j] = j < c.L ? j : -1;
+        if (tid == 0) { c.cnt[0] = c.L; c.cnt[1] = 0; c.cnt[2] = 0; c.cnt[3] = 0; }
+        return;
+    }
+    c.P = c.L - c.R;  // rankable prefix
+    c.mod = p.modality + seq0;
+    c.sc_self = p.score_self + (size_t)sg * p.total_tokens + seq0;
+    c.sc_cross = p.score_cross + (size_t)sg * p.total_tokens + seq0;
+
+    if (tid < 2) sh.has[tid] = 0;
     __syncthreads();
-    if (lane == 0) wcnt[0][wave] = n_both;
+    for (int i = tid; i < p.O; i += kSelThreads) atomicOr(&sh.has[c.mod[c.L - p.O + i] ? 1 : 0], 1u);
     __syncthreads();
-    if (tid == 0) {
-        uint32_t both = 0;
-        for (int w = 0; w < kSelWaves; ++w) both += wcnt[0][w];
-        cnt[0] = (int32_t)base_out; cnt[1] = K_s; cnt[2] = K_c; cnt[3] = (int32_t)both;
+    c.has0 = sh.has[0] != 0;
+    c.has1 = sh.has[1] != 0;
+
+    if (c.has0 && c.has1) {
+        select_body<4, true, false>(c, sh);       // both regions cover every key: two patterns per key
+    } else if (c.L <= kSelThreads * ITEMS) {
+        select_body<ITEMS, false, true>(c, sh);   // one super-block, patterns stay in registers
+    } else {
+        select_body<8, false, false>(c, sh);      // long sequence: super-blocks re-read per pass
     }
 }
 
 }  // namespace
 
-hipError_t launch_select(const SelectParams& p, hipStream_t s) {
-    const dim3 grid(p.H_sel, p.B);
-    hipLaunchKernelGGL(select_kernel, grid, dim3(kSelThreads), 0, s, p);
+#ifdef CSP_SEL_TRACE
+extern "C" int csp_debug_sel_trace(long long* out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_sel_trace), sizeof(long long) * 32); }
+#endif
+
+hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s) {
+    const dim3 grid(p.H_sel, p.B), block(kSelThreads);
+    const int items = (max_seqlen + kSelThreads - 1) / kSelThreads;
+    if (items <= 4) hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, s, p);
+    else if (items <= 8) hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, s, p);
+    else hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, s, p);  // longer than 16K keys: several super-blocks
     return hipGetLastError();
 }
 
