@@ -16,8 +16,10 @@
 // only the operand order of the MFMA differs.
 // A workgroup is 4 wavefronts; each wavefront owns a contiguous run of keys of
 // the workgroup's chunk and streams it in tiles of 32 keys: coalesced 16-byte
-// global loads (4 full 256-byte rows per instruction for bf16/D=128) into
-// registers one tile ahead, a wave-private padded LDS tile as the transpose
+// global loads (4 full 256-byte rows per instruction for bf16/D=128) into a
+// ring of register tiles PF tiles ahead (the loop is bound by HBM latency: the
+// bytes in flight per compute unit, not the arithmetic, set the rate), a
+// wave-private padded LDS tile as the transpose
 // between the load layout and the MFMA operand layout, no workgroup barrier
 // in the loop.  All exponentials are base 2 with log2(e)/sqrt(D) folded into
 // one FMA per element.
@@ -29,6 +31,17 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWaves = 4;
 constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
+
+// Prefetch depth (tiles in flight per wavefront) of the two passes for 2-byte elements.
+#ifndef CSP_SCORE_PF_A
+#define CSP_SCORE_PF_A 2
+#endif
+#ifndef CSP_SCORE_PF_B
+#define CSP_SCORE_PF_B 2
+#endif
+template <typename E> struct Prefetch;
+template <> struct Prefetch<bf16_tag> { static constexpr int A = CSP_SCORE_PF_A, B = CSP_SCORE_PF_B; };
+template <> struct Prefetch<f32_tag> { static constexpr int A = 1, B = 1; };  // 4-byte rows: 64 registers per tile
 
 template <typename E, int D>
 struct Geom {
@@ -62,11 +75,13 @@ __device__ __forceinline__ void wave_lds_sync() {
 // ---- query fragments --------------------------------------------------------
 // MFMA operand layout (32 x KSTEP block): lane = (r = lane%32, half = lane/32)
 // holds row r, contraction elements [s*KSTEP + half*KSTEP/2, +KSTEP/2).
-template <typename E, int D, int NQB>
+// IN_LDS = false: fragments live in registers (bf16 only).  IN_LDS = true: staged once per
+// head in LDS by the whole workgroup (caller barriers) and fetched per MFMA.
+template <typename E, int D, int NQB, bool IN_LDS>
 struct QFrags;
 
 template <int D, int NQB>
-struct QFrags<bf16_tag, D, NQB> {
+struct QFrags<bf16_tag, D, NQB, false> {
     bf16x8 f[NQB][D / 16];
     // qhead: [O][D] bf16 of one head.  Rows >= O read as zero.
     __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* /*q_lds*/) {
@@ -82,12 +97,37 @@ struct QFrags<bf16_tag, D, NQB> {
             }
     }
     __device__ __forceinline__ bf16x8 get(int nb, int s, int /*lane*/, const float* /*q_lds*/) const { return f[nb][s]; }
-    static constexpr bool kUsesLds = false;
+    static constexpr int kLdsBytes = 0;
 };
 
+// bf16 queries in LDS, already in operand order: fragment (nb, s) of lane l is the 16 bytes at
+// ((nb*NK + s)*64 + l)*16, so a wavefront fetch is one contiguous, conflict-free 1 KiB read.
 template <int D, int NQB>
-struct QFrags<f32_tag, D, NQB> {
-    // fp32 queries are staged in LDS by the whole workgroup (caller barriers).
+struct QFrags<bf16_tag, D, NQB, true> {
+    static constexpr int NK = D / 16;
+    __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* q_lds) {
+        constexpr int IT = NQB * NK * 64 / kThreads;  // 16-byte pieces per thread
+        u32x4 w[IT];
+#pragma unroll
+        for (int k = 0; k < IT; ++k) {                // all loads first, then all LDS writes
+            const int e = tid + k * kThreads;
+            const int l = e & 63, s = (e >> 6) % NK, nb = e / (64 * NK);
+            const int row = nb * 32 + (l & 31);
+            w[k] = u32x4{0u, 0u, 0u, 0u};
+            if (row < O) w[k] = *reinterpret_cast<const u32x4*>(qhead + ((size_t)row * D + s * 16 + (l >> 5) * 8) * 2);
+        }
+#pragma unroll
+        for (int k = 0; k < IT; ++k) reinterpret_cast<u32x4*>(q_lds)[tid + k * kThreads] = w[k];
+    }
+    __device__ __forceinline__ bf16x8 get(int nb, int s, int lane, const float* q_lds) const {
+        return reinterpret_cast<const bf16x8*>(q_lds)[(nb * NK + s) * 64 + lane];
+    }
+    static constexpr int kLdsBytes = NQB * NK * 64 * 16;
+};
+
+template <int D, int NQB, bool IN_LDS>
+struct QFrags<f32_tag, D, NQB, IN_LDS> {
+    // fp32 queries are always staged in LDS (row-major, padded rows).
     __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* q_lds) {
         constexpr int C4 = D / 4;
         for (int idx = tid; idx < NQB * 32 * C4; idx += kThreads) {
@@ -100,7 +140,7 @@ struct QFrags<f32_tag, D, NQB> {
     __device__ __forceinline__ float get(int nb, int s, int lane, const float* q_lds) const {
         return q_lds[(nb * 32 + (lane & 31)) * Geom<f32_tag, D>::QSTRIDE + s * 2 + (lane >> 5)];
     }
-    static constexpr bool kUsesLds = true;
+    static constexpr int kLdsBytes = NQB * 32 * Geom<f32_tag, D>::QSTRIDE * 4;
 };
 
 template <typename E, int D>
@@ -140,14 +180,14 @@ __device__ __forceinline__ void store_tile(const u32x4 (&st)[(Geom<E, D>::NLD)],
 // register-indexed axis (the other axis is lane%32)
 __device__ __forceinline__ int acc_row(int v, int half) { return (v >> 2) * 8 + half * 4 + (v & 3); }
 
-template <typename E, int D, int NQB>
+template <typename E, int D, int NQB, bool Q_IN_LDS>
 struct Smem {
     using G = Geom<E, D>;
     static constexpr int kTiles = kWaves * G::TILE_LDS;
     static constexpr int kRed = kWaves * NQB * 32 * 8;    // float2 per (wave, query)
     static constexpr int kNlse = NQB * 32 * 4;
     static constexpr int kWq = NQB * 32;                   // uint8 modality of window rows
-    static constexpr int kQ = QFrags<E, D, NQB>::kUsesLds ? NQB * 32 * G::QSTRIDE * 4 : 0;
+    static constexpr int kQ = QFrags<E, D, NQB, Q_IN_LDS>::kLdsBytes;
     static constexpr int off_red = kTiles;
     static constexpr int off_nlse = off_red + kRed;
     static constexpr int off_wq = off_nlse + kNlse;
@@ -159,9 +199,10 @@ struct Smem {
 // Pass A: per (sequence, query head, chunk) partial row statistics.
 // ---------------------------------------------------------------------------
 template <typename E, int D, int NQB>
-__global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreParams p) {
+__global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_stats_kernel(ScoreParams p) {
     using G = Geom<E, D>;
-    using SM = Smem<E, D, NQB>;
+    using QF = QFrags<E, D, NQB, false>;   // bf16: query fragments in registers
+    using SM = Smem<E, D, NQB, false>;
     extern __shared__ __align__(16) char smem[];
     const int chunk = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -176,10 +217,6 @@ __global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreParams p) {
     char* tile = smem + wave * G::TILE_LDS;
     float2* red = reinterpret_cast<float2*>(smem + SM::off_red);
     float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
-
-    QFrags<E, D, NQB> qf;
-    qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
-    if constexpr (QFrags<E, D, NQB>::kUsesLds) __syncthreads();
 
     const int hk = hq / p.G;
     const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
@@ -200,49 +237,84 @@ __global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreParams p) {
     }
     const int mask_from = p.causal ? L - O : L;  // keys below this index are visible to every row
 
-    u32x4 st[G::NLD];
-    if (ntiles > 0) load_tile<E, D>(st, kbase, tok_bytes, jb, L, lane);
-    for (int t = 0; t < ntiles; ++t) {
-        const int j0 = jb + t * kTile;
-        wave_lds_sync();
-        store_tile<E, D>(st, tile, lane);
-        wave_lds_sync();
-        if (t + 1 < ntiles) load_tile<E, D>(st, kbase, tok_bytes, j0 + kTile, L, lane);
-
-        f32x16 acc[NQB];
+    // Ring of PF register tiles.  Every iteration issues exactly one tile of loads, valid or
+    // not (rows past the end re-read row L-1, an L2 hit), so the number of loads in flight is
+    // the same on every path and the wait before a tile is used covers that tile only.
+    constexpr int PF = Prefetch<E>::A;
+    u32x4 st[PF][G::NLD];
+    // Tiles are visited in a rotated order (tile (t + rot) mod ntiles at step t) with a
+    // different rotation per wavefront and workgroup: all key runs are aligned to large powers
+    // of two, and wavefronts walking them in lockstep would hit the same memory channels.
+    const int rot = ntiles > 0 ? (int)((wave * 3u + chunk * 5u + hq * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
+        const int tt = t + rot;
+        return t < ntiles ? jb + (tt < ntiles ? tt : tt - ntiles) * kTile : L - 1;
+    };
+    // the key stream starts first; the queries (L2-resident, small) follow
+    if (ntiles > 0) {
 #pragma unroll
-        for (int nb = 0; nb < NQB; ++nb)
+        for (int u = 0; u < PF; ++u) load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
+    }
+    QF qf;
+    qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
+    if constexpr (QF::kLdsBytes > 0) __syncthreads();
+    if (ntiles > 0) {
+    for (int t0 = 0; t0 < ntiles; t0 += PF) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
-#pragma unroll
-        for (int s = 0; s < G::NK; ++s) {
-            const auto kf = k_frag<E, D>(tile, s, lane);
-#pragma unroll
-            for (int nb = 0; nb < NQB; ++nb) acc[nb] = mma(kf, qf.get(nb, s, lane, q_lds), acc[nb]);
-        }
-        // acc[nb][v]: key j0 + acc_row(v, half), query nb*32 + lane%32
-        const bool need_mask = j0 + kTile > mask_from;
-#pragma unroll
-        for (int nb = 0; nb < NQB; ++nb) {
-            float mx = NEG_INF;
-            if (need_mask) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int j = j0 + acc_row(v, half);
-                    const bool ok = j < L && (!p.causal || j <= pos_q[nb]);
-                    acc[nb][v] = ok ? acc[nb][v] : NEG_INF;
-                }
+        for (int u = 0; u < PF; ++u) {
+            const int t = t0 + u;
+            const int j0 = tile_key(t);
+            const bool live = t < ntiles;  // uniform
+            if (live) {
+                wave_lds_sync();
+                store_tile<E, D>(st[u], tile, lane);
+                wave_lds_sync();
             }
+#ifndef CSP_DBG_NO_LOAD
+            load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
+#endif
+            if (!live) continue;
+#ifdef CSP_DBG_NO_COMPUTE
+            l_run[0] += __uint_as_float(st[u][0][0]) + *reinterpret_cast<const float*>(tile + lane * 4);
+            continue;
+#endif
+
+            f32x16 acc[NQB];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[nb][v]);
-            const float mnew = fmaxf(m_run[nb], mx * c);
-            const float msafe = mnew == NEG_INF ? 0.f : mnew;
-            float sum = 0.f;
+            for (int nb = 0; nb < NQB; ++nb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(acc[nb][v], c, -msafe));
-            l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - msafe) + sum;
-            m_run[nb] = mnew;
+                for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < G::NK; ++s) {
+                const auto kf = k_frag<E, D>(tile, s, lane);
+#pragma unroll
+                for (int nb = 0; nb < NQB; ++nb) acc[nb] = mma(kf, qf.get(nb, s, lane, q_lds), acc[nb]);
+            }
+            // acc[nb][v]: key j0 + acc_row(v, half), query nb*32 + lane%32
+            const bool need_mask = j0 + kTile > mask_from;
+#pragma unroll
+            for (int nb = 0; nb < NQB; ++nb) {
+                float mx = NEG_INF;
+                if (need_mask) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int j = j0 + acc_row(v, half);
+                        const bool ok = j < L && (!p.causal || j <= pos_q[nb]);
+                        acc[nb][v] = ok ? acc[nb][v] : NEG_INF;
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[nb][v]);
+                const float mnew = fmaxf(m_run[nb], mx * c);
+                const float msafe = mnew == NEG_INF ? 0.f : mnew;
+                float sum = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(acc[nb][v], c, -msafe));
+                l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - msafe) + sum;
+                m_run[nb] = mnew;
+            }
         }
+    }
     }
 
     // combine the two lane halves, then the four wavefronts
@@ -276,9 +348,10 @@ __global__ __launch_bounds__(kThreads) void score_stats_kernel(ScoreParams p) {
 // Pass B: per (sequence, selection group, chunk) column sums.
 // ---------------------------------------------------------------------------
 template <typename E, int D, int NQB>
-__global__ __launch_bounds__(kThreads) void score_colsum_kernel(ScoreParams p) {
+__global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kernel(ScoreParams p) {
     using G = Geom<E, D>;
-    using SM = Smem<E, D, NQB>;
+    using QF = QFrags<E, D, NQB, true>;    // query fragments in LDS: frees 32*NQB registers for the prefetch ring
+    using SM = Smem<E, D, NQB, true>;
     extern __shared__ __align__(16) char smem[];
     const int chunk = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -323,115 +396,163 @@ __global__ __launch_bounds__(kThreads) void score_colsum_kernel(ScoreParams p) {
     const int mask_from = min(rank_end, p.causal ? L - O : L);    // below: no masking needed
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
+    constexpr int PF = Prefetch<E>::B;
+    // same rotated visiting order as pass A (the two passes need not agree)
+    const int rot = ntiles > 0 ? (int)((wave * 3u + chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
+        const int tt = t + rot;
+        return t < ntiles ? jb + (tt < ntiles ? tt : tt - ntiles) * kTile : L - 1;
+    };
+    auto load_mod = [&](int j0) -> uint8_t {  // modality of key j0 + lane%32, fetched with its tile
+        const int j = j0 + (lane & 31);
+        return p.modality[seq0 + (j < L ? j : L - 1)];
+    };
+
     for (int g = 0; g < p.sel_group; ++g) {
         const int hq = sg * p.sel_group + g;
         const int hk = hq / p.G;
+        // the key stream starts first; the per-head set-up below overlaps with it
+        const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
+        u32x4 st[PF][G::NLD];
+        uint8_t kmod[PF];
+        if (ntiles > 0) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
+                kmod[u] = load_mod(tile_key(u));
+            }
+        }
         __syncthreads();  // previous head's nlse_s / q_lds are no longer read
         if (tid < NQB * 32) {
             float nl = NEG_INF;
             if (tid < O) {
                 const float2* part = reinterpret_cast<const float2*>(p.part) + ((size_t)(b * p.H_q + hq) * p.n_chunks) * O + tid;
-                float M = NEG_INF;
-                for (int ch = 0; ch < n_chunks_b; ++ch) M = fmaxf(M, part[(size_t)ch * O].x);
-                float Ls = 0.f;
-                for (int ch = 0; ch < n_chunks_b; ++ch) {
-                    const float2 r = part[(size_t)ch * O];
-                    Ls += r.y * fast_exp2(r.x - M);
+                // merge of the chunk partials (max, sum): 8 independent loads at a time
+                float M = NEG_INF, Ls = 0.f;
+                for (int ch0 = 0; ch0 < n_chunks_b; ch0 += 8) {
+                    float2 r[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        r[u] = ch0 + u < n_chunks_b ? part[(size_t)(ch0 + u) * O] : make_float2(NEG_INF, 0.f);
+                    float Mn = M;
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) Mn = fmaxf(Mn, r[u].x);
+                    Ls *= fast_exp2(M - Mn);   // chunk 0 always holds a visible key, so Mn is finite
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) Ls += r[u].y * fast_exp2(r[u].x - Mn);
+                    M = Mn;
                 }
                 Ls += p.n_score * fast_exp2(-M);  // the n of the n-softmax, in the same scaled units
                 nl = -(M + fast_log2(Ls)) / c;  // in units of the raw dot product: seeds the accumulator
             }
             nlse_s[tid] = nl;
         }
-        QFrags<E, D, NQB> qf;
+        QF qf;
         qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
         __syncthreads();
-        const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
-        u32x4 st[G::NLD];
-        if (ntiles > 0) load_tile<E, D>(st, kbase, tok_bytes, jb, L, lane);
-        for (int t = 0; t < ntiles; ++t) {
-            const int j0 = jb + t * kTile;
-            wave_lds_sync();
-            store_tile<E, D>(st, tile, lane);
-            wave_lds_sync();
-            if (t + 1 < ntiles) load_tile<E, D>(st, kbase, tok_bytes, j0 + kTile, L, lane);
+        if (ntiles > 0) {
+        for (int t0 = 0; t0 < ntiles; t0 += PF) {
+#pragma unroll
+            for (int u = 0; u < PF; ++u) {
+                const int t = t0 + u;
+                const int j0 = tile_key(t);
+                const bool live = t < ntiles;  // uniform
+                if (live) {
+                    wave_lds_sync();
+                    store_tile<E, D>(st[u], tile, lane);
+                    wave_lds_sync();
+                }
+                const bool key_text = kmod[u] == 0;
+                // one tile of loads per iteration on every path (see the ring in pass A)
+#ifndef CSP_DBG_NO_LOAD
+                load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
+                kmod[u] = load_mod(tile_key(t + PF));
+#endif
+                if (!live) continue;
+#ifdef CSP_DBG_NO_COMPUTE
+                if (half == 0 && j0 + (lane & 31) < L)
+                    p.score_self[(size_t)sg * p.total_tokens + seq0 + j0 + (lane & 31)] = __uint_as_float(st[u][0][0]) + *reinterpret_cast<const float*>(tile + lane * 4) + (key_text ? 1.f : 0.f);
+                continue;
+#endif
 
-            // the accumulator starts at -lse_i/c, so that 2^(c*acc) is the normalised weight
-            f32x16 acc[NQB];
+                // the accumulator starts at -lse_i/c, so that 2^(c*acc) is the normalised weight
+                f32x16 acc[NQB];
 #pragma unroll
-            for (int mb = 0; mb < NQB; ++mb)
+                for (int mb = 0; mb < NQB; ++mb)
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const float4 w = *reinterpret_cast<const float4*>(nlse_s + mb * 32 + v4 * 8 + half * 4);
-                    acc[mb][v4 * 4 + 0] = w.x; acc[mb][v4 * 4 + 1] = w.y;
-                    acc[mb][v4 * 4 + 2] = w.z; acc[mb][v4 * 4 + 3] = w.w;
-                }
-#pragma unroll
-            for (int s = 0; s < G::NK; ++s) {
-                const auto kf = k_frag<E, D>(tile, s, lane);
-#pragma unroll
-                for (int mb = 0; mb < NQB; ++mb) acc[mb] = mma(qf.get(mb, s, lane, q_lds), kf, acc[mb]);
-            }
-            // acc[mb][v]: query mb*32 + acc_row(v, half), key j0 + lane%32
-            const int j = j0 + (lane & 31);
-            const bool need_mask = j0 + kTile > mask_from;
-            float ct = 0.f, cv = 0.f;  // sums over text / visual window rows
-#pragma unroll
-            for (int mb = 0; mb < NQB; ++mb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float pv = fast_exp2(acc[mb][v] * c);
-                    if (need_mask) {
-                        const int i = mb * 32 + acc_row(v, half);
-                        const bool ok = j < rank_end && (!p.causal || j <= L - O + i);
-                        pv = ok ? pv : 0.f;
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        const float4 w = *reinterpret_cast<const float4*>(nlse_s + mb * 32 + v4 * 8 + half * 4);
+                        acc[mb][v4 * 4 + 0] = w.x; acc[mb][v4 * 4 + 1] = w.y;
+                        acc[mb][v4 * 4 + 2] = w.z; acc[mb][v4 * 4 + 3] = w.w;
                     }
-                    if (mixed) {
-                        const bool is_text = (text_bits[mb / 2] >> ((mb & 1) * 16 + v)) & 1u;
-                        ct += is_text ? pv : 0.f;
-                        cv += is_text ? 0.f : pv;
-                    } else {
-                        ct += pv;
+#pragma unroll
+                for (int s = 0; s < G::NK; ++s) {
+                    const auto kf = k_frag<E, D>(tile, s, lane);
+#pragma unroll
+                    for (int mb = 0; mb < NQB; ++mb) acc[mb] = mma(qf.get(mb, s, lane, q_lds), kf, acc[mb]);
+                }
+                // acc[mb][v]: query mb*32 + acc_row(v, half), key j0 + lane%32
+                const int j = j0 + (lane & 31);
+                const bool need_mask = j0 + kTile > mask_from;
+                float ct = 0.f, cv = 0.f;  // sums over text / visual window rows
+#pragma unroll
+                for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float pv = fast_exp2(acc[mb][v] * c);
+                        if (need_mask) {
+                            const int i = mb * 32 + acc_row(v, half);
+                            const bool ok = j < rank_end && (!p.causal || j <= L - O + i);
+                            pv = ok ? pv : 0.f;
+                        }
+                        if (mixed) {
+                            const bool is_text = (text_bits[mb / 2] >> ((mb & 1) * 16 + v)) & 1u;
+                            ct += is_text ? pv : 0.f;
+                            cv += is_text ? 0.f : pv;
+                        } else {
+                            ct += pv;
+                        }
                     }
+                ct += __shfl_xor(ct, 32);
+                if (mixed) cv += __shfl_xor(cv, 32);
+                else if (any_vis) { cv = ct; ct = 0.f; }  // an all-visual window: every row is a visual query
+                if (half == 0 && j < L) {
+                    float s_self = key_text ? ct : cv;
+                    float s_cross = key_text ? cv : ct;
+                    const size_t o = (size_t)sg * p.total_tokens + seq0 + j;
+                    if (g > 0) {  // same thread wrote these in the previous head iteration
+                        s_self += p.score_self[o];
+                        s_cross += p.score_cross[o];
+                    }
+                    p.score_self[o] = s_self;
+                    p.score_cross[o] = s_cross;
                 }
-            ct += __shfl_xor(ct, 32);
-            if (mixed) cv += __shfl_xor(cv, 32);
-            else if (any_vis) { cv = ct; ct = 0.f; }  // an all-visual window: every row is a visual query
-            if (half == 0 && j < L) {
-                const bool key_text = p.modality[seq0 + j] == 0;
-                float s_self = key_text ? ct : cv;
-                float s_cross = key_text ? cv : ct;
-                const size_t o = (size_t)sg * p.total_tokens + seq0 + j;
-                if (g > 0) {  // same thread wrote these in the previous head iteration
-                    s_self += p.score_self[o];
-                    s_cross += p.score_cross[o];
-                }
-                p.score_self[o] = s_self;
-                p.score_cross[o] = s_cross;
             }
+        }
         }
     }
 }
 
 template <typename E, int D, int NQB>
 hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
-    using SM = Smem<E, D, NQB>;
-    const size_t smem = SM::total;
+    const size_t smem_a = Smem<E, D, NQB, false>::total, smem_b = Smem<E, D, NQB, true>::total;
     auto ka = score_stats_kernel<E, D, NQB>;
     auto kb = score_colsum_kernel<E, D, NQB>;
-    if (smem > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ka), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (smem_a > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ka), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_a);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kb), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    }
+    if (smem_b > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kb), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_b);
         if (e != hipSuccess) return e;
     }
     const dim3 block(kThreads);
     const dim3 grid_a(p.n_chunks, p.H_q, p.B);
     const dim3 grid_b(p.n_chunks, p.H_q / p.sel_group, p.B);
-    hipLaunchKernelGGL(ka, grid_a, block, smem, s, p);
+    hipLaunchKernelGGL(ka, grid_a, block, smem_a, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kb, grid_b, block, smem, s, p);
+    hipLaunchKernelGGL(kb, grid_b, block, smem_b, s, p);
     return hipGetLastError();
 }
 
