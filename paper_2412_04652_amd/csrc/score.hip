@@ -37,8 +37,14 @@ constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
 #define CSP_SCORE_PF_A 2
 #endif
 #ifndef CSP_SCORE_PF_B
-#define CSP_SCORE_PF_B 2
+#define CSP_SCORE_PF_B 1
 #endif
+// Pass B query fragments: registers (0) or LDS in operand order (1, frees 32*NQB registers
+// at the price of 16 KiB of LDS reads per tile).
+#ifndef CSP_SCORE_QB_LDS
+#define CSP_SCORE_QB_LDS 0
+#endif
+constexpr bool kQbLds = CSP_SCORE_QB_LDS != 0;
 template <typename E> struct Prefetch;
 template <> struct Prefetch<bf16_tag> { static constexpr int A = CSP_SCORE_PF_A, B = CSP_SCORE_PF_B; };
 template <> struct Prefetch<f32_tag> { static constexpr int A = 1, B = 1; };  // 4-byte rows: 64 registers per tile
@@ -195,6 +201,43 @@ struct Smem {
     static constexpr int total = off_q + kQ;
 };
 
+// Online (max, sum-exp) update of this lane's rows with one key tile.  MASK: some keys of the
+// tile are past the end of the sequence or not visible to some rows (causal tail).
+template <int NQB, bool MASK>
+__device__ __forceinline__ void stats_tile(f32x16 (&acc)[NQB], float c, int j0, int half, int L, int causal,
+                                           const int (&pos_q)[NQB], float (&m_run)[NQB], float (&l_run)[NQB]) {
+    const float NEG_INF = -__builtin_inff();
+#pragma unroll
+    for (int nb = 0; nb < NQB; ++nb) {
+        if constexpr (MASK) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int j = j0 + acc_row(v, half);
+                const bool ok = j < L && (!causal || j <= pos_q[nb]);
+                acc[nb][v] = ok ? acc[nb][v] : NEG_INF;
+            }
+        }
+        float mx0 = fmaxf(acc[nb][0], acc[nb][1]), mx1 = fmaxf(acc[nb][2], acc[nb][3]);
+#pragma unroll
+        for (int v = 4; v < 16; v += 4) {
+            mx0 = fmaxf(mx0, fmaxf(acc[nb][v], acc[nb][v + 1]));      // v_max3
+            mx1 = fmaxf(mx1, fmaxf(acc[nb][v + 2], acc[nb][v + 3]));
+        }
+        const float mnew = fmaxf(m_run[nb], fmaxf(mx0, mx1) * c);
+        const float msafe = mnew == NEG_INF ? 0.f : mnew;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;  // four add chains
+#pragma unroll
+        for (int v = 0; v < 16; v += 4) {
+            s0 += fast_exp2(fmaf(acc[nb][v], c, -msafe));
+            s1 += fast_exp2(fmaf(acc[nb][v + 1], c, -msafe));
+            s2 += fast_exp2(fmaf(acc[nb][v + 2], c, -msafe));
+            s3 += fast_exp2(fmaf(acc[nb][v + 3], c, -msafe));
+        }
+        l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - msafe) + ((s0 + s1) + (s2 + s3));
+        m_run[nb] = mnew;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Pass A: per (sequence, query head, chunk) partial row statistics.
 // ---------------------------------------------------------------------------
@@ -291,28 +334,8 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_stats_kernel
                 for (int nb = 0; nb < NQB; ++nb) acc[nb] = mma(kf, qf.get(nb, s, lane, q_lds), acc[nb]);
             }
             // acc[nb][v]: key j0 + acc_row(v, half), query nb*32 + lane%32
-            const bool need_mask = j0 + kTile > mask_from;
-#pragma unroll
-            for (int nb = 0; nb < NQB; ++nb) {
-                float mx = NEG_INF;
-                if (need_mask) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int j = j0 + acc_row(v, half);
-                        const bool ok = j < L && (!p.causal || j <= pos_q[nb]);
-                        acc[nb][v] = ok ? acc[nb][v] : NEG_INF;
-                    }
-                }
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, acc[nb][v]);
-                const float mnew = fmaxf(m_run[nb], mx * c);
-                const float msafe = mnew == NEG_INF ? 0.f : mnew;
-                float sum = 0.f;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sum += fast_exp2(fmaf(acc[nb][v], c, -msafe));
-                l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - msafe) + sum;
-                m_run[nb] = mnew;
-            }
+            if (j0 + kTile > mask_from) stats_tile<NQB, true>(acc, c, j0, half, L, p.causal, pos_q, m_run, l_run);
+            else stats_tile<NQB, false>(acc, c, j0, half, L, p.causal, pos_q, m_run, l_run);
         }
     }
     }
@@ -344,14 +367,48 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_stats_kernel
     }
 }
 
+// Sum over the window rows held by this lane of 2^(c*acc) for one key tile.  MASK: rows may not
+// see the key (causal tail) or the key is not ranked; MIXED: the window holds both modalities
+// and text / visual rows are summed apart (ct / cv), otherwise everything goes to ct.
+template <int NQB, bool MASK, bool MIXED>
+__device__ __forceinline__ void colsum_tile(const f32x16 (&acc)[NQB], float c, const uint32_t (&text_bits)[(NQB + 1) / 2],
+                                            int j, int half, int rank_end, int first_pos, int causal,
+                                            float& ct, float& cv) {
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;  // four add chains
+    float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float pv = fast_exp2(acc[mb][v] * c);
+            if constexpr (MASK) {
+                const int i = mb * 32 + acc_row(v, half);
+                const bool ok = j < rank_end && (!causal || j <= first_pos + i);
+                pv = ok ? pv : 0.f;
+            }
+            if constexpr (MIXED) {
+                const bool is_text = (text_bits[mb / 2] >> ((mb & 1) * 16 + v)) & 1u;
+                if (v & 1) { t1 += is_text ? pv : 0.f; s1 += is_text ? 0.f : pv; }
+                else { t0 += is_text ? pv : 0.f; s0 += is_text ? 0.f : pv; }
+            } else {
+                if ((v & 3) == 0) s0 += pv;
+                else if ((v & 3) == 1) s1 += pv;
+                else if ((v & 3) == 2) s2 += pv;
+                else s3 += pv;
+            }
+        }
+    if constexpr (MIXED) { ct = t0 + t1; cv = s0 + s1; }
+    else { ct = (s0 + s1) + (s2 + s3); cv = 0.f; }
+}
+
 // ---------------------------------------------------------------------------
 // Pass B: per (sequence, selection group, chunk) column sums.
 // ---------------------------------------------------------------------------
 template <typename E, int D, int NQB>
 __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kernel(ScoreParams p) {
     using G = Geom<E, D>;
-    using QF = QFrags<E, D, NQB, true>;    // query fragments in LDS: frees 32*NQB registers for the prefetch ring
-    using SM = Smem<E, D, NQB, true>;
+    using QF = QFrags<E, D, NQB, kQbLds>;
+    using SM = Smem<E, D, NQB, kQbLds>;
     extern __shared__ __align__(16) char smem[];
     const int chunk = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -449,7 +506,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kerne
         }
         QF qf;
         qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
-        __syncthreads();
+        __syncthreads();  // nlse_s (and staged queries) visible
         if (ntiles > 0) {
         for (int t0 = 0; t0 < ntiles; t0 += PF) {
 #pragma unroll
@@ -495,24 +552,15 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kerne
                 const int j = j0 + (lane & 31);
                 const bool need_mask = j0 + kTile > mask_from;
                 float ct = 0.f, cv = 0.f;  // sums over text / visual window rows
-#pragma unroll
-                for (int mb = 0; mb < NQB; ++mb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float pv = fast_exp2(acc[mb][v] * c);
-                        if (need_mask) {
-                            const int i = mb * 32 + acc_row(v, half);
-                            const bool ok = j < rank_end && (!p.causal || j <= L - O + i);
-                            pv = ok ? pv : 0.f;
-                        }
-                        if (mixed) {
-                            const bool is_text = (text_bits[mb / 2] >> ((mb & 1) * 16 + v)) & 1u;
-                            ct += is_text ? pv : 0.f;
-                            cv += is_text ? 0.f : pv;
-                        } else {
-                            ct += pv;
-                        }
-                    }
+                // four straight-line variants behind uniform branches (masking only touches the
+                // last tiles of a sequence, a window with both modalities is rare)
+                if (!need_mask) {
+                    if (!mixed) colsum_tile<NQB, false, false>(acc, c, text_bits, j, half, rank_end, L - O, p.causal, ct, cv);
+                    else colsum_tile<NQB, false, true>(acc, c, text_bits, j, half, rank_end, L - O, p.causal, ct, cv);
+                } else {
+                    if (!mixed) colsum_tile<NQB, true, false>(acc, c, text_bits, j, half, rank_end, L - O, p.causal, ct, cv);
+                    else colsum_tile<NQB, true, true>(acc, c, text_bits, j, half, rank_end, L - O, p.causal, ct, cv);
+                }
                 ct += __shfl_xor(ct, 32);
                 if (mixed) cv += __shfl_xor(cv, 32);
                 else if (any_vis) { cv = ct; ct = 0.f; }  // an all-visual window: every row is a visual query
@@ -535,7 +583,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kerne
 
 template <typename E, int D, int NQB>
 hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
-    const size_t smem_a = Smem<E, D, NQB, false>::total, smem_b = Smem<E, D, NQB, true>::total;
+    const size_t smem_a = Smem<E, D, NQB, false>::total, smem_b = Smem<E, D, NQB, kQbLds>::total;
     auto ka = score_stats_kernel<E, D, NQB>;
     auto kb = score_colsum_kernel<E, D, NQB>;
     if (smem_a > 64 * 1024) {
