@@ -1,0 +1,142 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (same descriptor, same grids): inputs are drawn on
+the device with the workload recipe, the rows of a sample of (sequence, head)
+problems are copied back, and the oracle checks those problems one by one."""
+import numpy as np
+import pytest
+
+import csp_workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2412_04652_amd as P
+    P.load_library()
+    return torch.device("cuda:0")
+
+
+def _bits(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _check_sample(oracle, U, lay, q, k, v, mod, cu, sample, *, O, R, T_of, G, sel_group, dec, what):
+    """sample: list of (b, s).  dec: (dq, dk, dv) device tensors of one decode step (appended, then attended)."""
+    g_self, g_cross = lay.score_self, lay.score_cross
+    idx_all, cnt_all = lay.kept_idx.cpu().numpy(), lay.kept_cnt.cpu().numpy()
+    kv_per_sel = sel_group // G
+    mod_h = mod.cpu().numpy()
+    out = lay.out.cpu().numpy()
+    n_diff = 0
+    for b, s in sample:
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        L, T = hi - lo, T_of(b)
+        m = mod_h[lo:hi]
+        a_s = np.zeros(L)
+        a_c = np.zeros(L)
+        for hq in range(s * sel_group, (s + 1) * sel_group):
+            oracle.head_scores(oracle.bf16_bits_to_f64(_bits(q[b, hq])), oracle.bf16_bits_to_f64(_bits(k[hq // G, lo:hi])),
+                               m, R, 0.0, True, a_s, a_c)
+        P = L - R
+        U.assert_scores_close(g_self[s, lo:lo + P].cpu().numpy(), a_s[:P], f"{what} b{b} s{s} self")
+        U.assert_scores_close(g_cross[s, lo:lo + P].cpu().numpy(), a_c[:P], f"{what} b{b} s{s} cross")
+        ref_idx, rc = oracle.select(a_s, a_c, m, O, R, T, 0.5)
+        n = int(cnt_all[b, s, 0])
+        assert n == rc["kept"] == min(T, L)
+        assert cnt_all[b, s, 1:3].tolist() == [rc["K_s"], rc["K_c"]]
+        n_diff += U.assert_kept_equivalent(idx_all[b, s, :n], ref_idx, a_s, a_c, m, L, R, f"{what} b{b} s{s}")
+        gi = idx_all[b, s, :n]
+        for hk in range(s * kv_per_sel, (s + 1) * kv_per_sel):
+            kh, vh = _bits(k[hk, lo:hi]), _bits(v[hk, lo:hi])
+            np.testing.assert_array_equal(_bits(lay.k_cache[b, hk, :n]), oracle.gather(kh, gi))
+            np.testing.assert_array_equal(_bits(lay.v_cache[b, hk, :n]), oracle.gather(vh, gi))
+            # decode step over the GPU's own pruned cache + the appended token
+            keys = np.concatenate([kh[gi], _bits(dec[1][b, hk])[None]])
+            vals = np.concatenate([vh[gi], _bits(dec[2][b, hk])[None]])
+            for hq in range(hk * G, (hk + 1) * G):
+                ref = oracle.decode(oracle.bf16_bits_to_f64(_bits(dec[0][b, hq])), oracle.bf16_bits_to_f64(keys),
+                                    oracle.bf16_bits_to_f64(vals), 1.0)
+                U.assert_decode_close(out[b, hq], ref, f"{what} decode b{b} h{hq}")
+    return n_diff
+
+
+def _run(gpu, layouts, *, H_q, H_kv, D, O, budgets, sel_group, seed, heavy=0.0):
+    from paper_2412_04652_amd.runner import CspLayer
+    q, k, v, mod, cu_dev, cu = W.device_qkv(layouts, H_q=H_q, H_kv=H_kv, D=D, O=O, seed=seed, device=gpu,
+                                            heavy_visual_frac=heavy)
+    lay = CspLayer(dtype="bf16", H_q=H_q, H_kv=H_kv, D=D, O=O, R=O, cu_seqlens=cu.tolist(), budgets=budgets,
+                   sel_group=sel_group, decode_cap=1, device=gpu)
+    g = torch.Generator(device=gpu); g.manual_seed(seed + 99)
+    B = len(layouts)
+    dq = torch.randn((B, H_q, D), generator=g, device=gpu).to(torch.bfloat16)
+    dk = torch.randn((B, H_kv, D), generator=g, device=gpu).to(torch.bfloat16)
+    dv = torch.randn((B, H_kv, D), generator=g, device=gpu).to(torch.bfloat16)
+    lay.prune(q, k, v, mod)
+    lay.append(dk, dv)
+    lay.decode(dq)
+    torch.cuda.synchronize()
+    return lay, q, k, v, mod, cu, (dq, dk, dv)
+
+
+@pytest.mark.parametrize("budget", [0.5, 0.2])
+def test_7b_16k_layer_sampled(gpu, oracle, budget):
+    """One layer of the benchmark workload: B=4, 32 heads, L=16384, D=128, window 64."""
+    import gpu_util as U
+    rng = np.random.default_rng(1000)
+    layouts = [W.layout_7b_16k(rng) for _ in range(4)]
+    T = int(16384 * budget)
+    print(f"[full] 7b_16k budget={budget} T={T}", flush=True)
+    lay, q, k, v, mod, cu, dec = _run(gpu, layouts, H_q=32, H_kv=32, D=128, O=64, budgets=[T] * 4, sel_group=1, seed=0)
+    sample = [(0, 0), (1, 13), (2, 31), (3, 7), (3, 20)]
+    nd = _check_sample(oracle, U, lay, q, k, v, mod, cu, sample, O=64, R=64, T_of=lambda b: T, G=1, sel_group=1,
+                       dec=dec, what=f"7b_16k@{budget}")
+    print(f"[full] keys differing near the threshold: {nd}", flush=True)
+    assert nd <= 4 * len(sample)
+    # properties that hold for every head, checked on all 128 of them
+    cnt = lay.kept_cnt.cpu().numpy()
+    assert (cnt[:, :, 0] == T).all() and (cnt[:, :, 1] + cnt[:, :, 2] == T - 64).all()
+    idx = lay.kept_idx.cpu().numpy()
+    assert (np.diff(idx, axis=-1) > 0).all() and (idx[:, :, -64:] == np.arange(16384 - 64, 16384)).all()
+    # softmax rows sum to one: the column sums over all ranked keys plus the recent keys' mass = O;
+    # so the ranked mass is at most O and, with 64 recent keys of 16384, close to it
+    tot = (lay.score_self + lay.score_cross).view(32, 4, 16384).sum(-1).cpu().numpy()
+    assert (tot <= 64 * (1 + 1e-3)).all() and (tot > 32).all()
+
+
+def test_64k_stress_sampled(gpu, oracle):
+    """B=1, 32 heads, L=65536, window 128, budget 10 %, 1 % of the visual keys scaled x4."""
+    import gpu_util as U
+    rng = np.random.default_rng(5)
+    layouts = [W.layout_64k(rng)]
+    T = 6553
+    print("[full] 64k stress", flush=True)
+    lay, q, k, v, mod, cu, dec = _run(gpu, layouts, H_q=32, H_kv=32, D=128, O=128, budgets=[T], sel_group=1, seed=3,
+                                      heavy=0.01)
+    nd = _check_sample(oracle, U, lay, q, k, v, mod, cu, [(0, 5), (0, 30)], O=128, R=128, T_of=lambda b: T, G=1,
+                       sel_group=1, dec=dec, what="64k")
+    print(f"[full] 64k keys differing near the threshold: {nd}", flush=True)
+    cnt = lay.kept_cnt.cpu().numpy()
+    assert (cnt[0, :, 0] == T).all() and (cnt[0, :, 1] == 3213).all() and (cnt[0, :, 2] == 3212).all()
+
+
+def test_gqa_ragged_full_sampled(gpu, oracle):
+    """B=8 ragged sequences up to 8192 tokens, 28 query heads on 4 KV heads, one index set per KV head."""
+    import gpu_util as U
+    rng = np.random.default_rng(1000)
+    layouts = [W.layout_gqa_ragged(rng, 8192) for _ in range(8)]
+    lens = [sum(n for _, n in s) for s in layouts]
+    budgets = [l // 2 for l in lens]
+    print(f"[full] gqa ragged lens={lens}", flush=True)
+    lay, q, k, v, mod, cu, dec = _run(gpu, layouts, H_q=28, H_kv=4, D=128, O=64, budgets=budgets, sel_group=7, seed=11)
+    sample = [(0, 0), (3, 2), (7, 3)]
+    _check_sample(oracle, U, lay, q, k, v, mod, cu, sample, O=64, R=64, T_of=lambda b: budgets[b], G=7, sel_group=7,
+                  dec=dec, what="gqa")
+    cnt = lay.kept_cnt.cpu().numpy()
+    for b in range(8):
+        assert (cnt[b, :, 0] == budgets[b]).all()
+    np.testing.assert_array_equal(lay.kv_len.cpu().numpy(), np.broadcast_to(np.array(budgets)[:, None] + 1, (8, 4)))
