@@ -117,12 +117,11 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8):
     n_call = 0
     for t in range(decode_steps):
         for li, lay in enumerate(layers):
-            lay.append(dec["k"][t % dec["n"]], dec["v"][t % dec["n"]])
             sampled = (n_call % sample_every) == 0
             n_call += 1
             if sampled:
                 e0, e1 = timer.span("decode_call"); e0.record()
-            lay.decode(dec["q"][t % dec["n"]])
+            lay.decode_step(dec["q"][t % dec["n"]], dec["k"][t % dec["n"]], dec["v"][t % dec["n"]])  # append + attend
             if sampled:
                 e1.record()
     b.record()
@@ -173,7 +172,7 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device):
         call_ms = avg(ms["decode_call"])
         res.update(decode_ms_per_token=dec_ms / decode_steps,
                    decode_gbps=by_decode * n_layers * decode_steps / (dec_ms * 1e-3) / 1e9)
-        res["kernels"]["decode_attn(split+merge)"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
+        res["kernels"]["decode_step(split+merge)"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
     del layers
     torch.cuda.empty_cache()
     return res

@@ -12,6 +12,7 @@
  *   csp_compact      gather of the kept K/V rows into the pruned cache
  *   csp_decode_attn  one decode step of n-softmax attention over that cache
  *   csp_append_kv    append the new token's k, v to the pruned cache
+ *   csp_decode_step  append + attend fused into one call
  *
  * Conventions
  *  - "device" pointers are HIP device memory owned by the caller; "host"
@@ -174,6 +175,21 @@ size_t csp_decode_workspace_bytes(const csp_desc* desc, int32_t max_kv_len);
 int csp_decode_attn(const csp_desc* desc, const void* q, const void* k_cache, const void* v_cache,
                     int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
                     const int32_t* kv_len, int32_t max_kv_len, float* out,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * csp_decode_step — csp_append_kv followed by csp_decode_attn in one call (one
+ * kernel launch fewer per decode step): the new token's key and value (device
+ * [B][H_kv][D]) are appended at row kv_len[b][h] of the pruned cache, attended
+ * to together with the rows before them (Eq. "n-softmax"), and kv_len[b][h] is
+ * incremented.  A slab that is already full (kv_len == cache_cap) is left
+ * unchanged and the new token is not attended to.  ws is sized by
+ * csp_decode_workspace_bytes(desc, cache_cap).  Other arguments as in
+ * csp_decode_attn / csp_append_kv.
+ * ---------------------------------------------------------------------- */
+int csp_decode_step(const csp_desc* desc, const void* q, const void* k_new, const void* v_new,
+                    void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                    int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, float* out,
                     void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------

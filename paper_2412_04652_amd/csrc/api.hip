@@ -177,22 +177,24 @@ size_t csp_decode_workspace_bytes(const csp_desc* d, int32_t max_kv_len) {
     return (size_t)d->B * d->H_q * ns * (d->D + 2) * sizeof(float);
 }
 
-int csp_decode_attn(const csp_desc* d, const void* q, const void* k_cache, const void* v_cache,
-                    int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
-                    const int32_t* kv_len, int32_t max_kv_len, float* out,
-                    void* ws, size_t ws_bytes, void* stream) {
+static int decode_common(const csp_desc* d, const void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                         int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, int32_t max_kv_len,
+                         float* out, void* ws, size_t ws_bytes, void* stream) {
     Checked c;
     int rc = check_desc(d, false, &c);
     if (rc != CSP_OK) return rc;
     if (!q || !k_cache || !v_cache || !kv_len || !out || max_kv_len <= 0) return CSP_EINVAL;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return CSP_EINVAL;
+    if (k_new && (!v_new || !aligned16(k_new) || !aligned16(v_new) || cache_cap <= 0)) return CSP_EINVAL;
     if ((rc = check_kv_strides(cache_stride_tok, cache_stride_head, d->D, c.EB)) != CSP_OK) return rc;
     if (cache_stride_b < 0 || (cache_stride_b * c.EB) % 16 != 0) return CSP_EINVAL;
     const size_t need = csp_decode_workspace_bytes(d, max_kv_len);
     if (!ws || ws_bytes < need || !aligned16(ws)) return CSP_EWORKSPACE;
     DecodeParams p;
     std::memset(&p, 0, sizeof(p));
-    p.q = q; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_len = kv_len; p.out = out;
+    p.q = q; p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_len = kv_len; p.out = out;
+    p.cache_cap = cache_cap;
     p.part = static_cast<float*>(ws);
     p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.G = c.G;
     p.n_splits = decode_num_splits(d->B, d->H_kv, max_kv_len);
@@ -201,6 +203,24 @@ int csp_decode_attn(const csp_desc* d, const void* q, const void* k_cache, const
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
     p.n_decode = (float)d->n_decode;
     return launch_decode(p, d->dtype, d->D, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+int csp_decode_attn(const csp_desc* d, const void* q, const void* k_cache, const void* v_cache,
+                    int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                    const int32_t* kv_len, int32_t max_kv_len, float* out,
+                    void* ws, size_t ws_bytes, void* stream) {
+    // attend only: nothing is written to the cache or to kv_len
+    return decode_common(d, q, nullptr, nullptr, const_cast<void*>(k_cache), const_cast<void*>(v_cache), cache_stride_b,
+                         cache_stride_head, cache_stride_tok, 0, const_cast<int32_t*>(kv_len), max_kv_len, out, ws,
+                         ws_bytes, stream);
+}
+
+int csp_decode_step(const csp_desc* d, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                    void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                    int32_t cache_cap, int32_t* kv_len, float* out, void* ws, size_t ws_bytes, void* stream) {
+    if (!k_new || !v_new) return CSP_EINVAL;
+    return decode_common(d, q, k_new, v_new, k_cache, v_cache, cache_stride_b, cache_stride_head, cache_stride_tok,
+                         cache_cap, kv_len, cache_cap, out, ws, ws_bytes, stream);
 }
 
 int csp_append_kv(const csp_desc* d, const void* k_new, const void* v_new, void* k_cache,

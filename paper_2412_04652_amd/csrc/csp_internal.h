@@ -85,9 +85,12 @@ struct AppendParams {
 
 struct DecodeParams {
     const void* q;
-    const void* k_cache;
-    const void* v_cache;
-    const int32_t* kv_len;
+    const void* k_new;    // fused append (csp_decode_step); nullptr = attend only
+    const void* v_new;
+    void* k_cache;
+    void* v_cache;
+    int32_t* kv_len;
+    int32_t cache_cap;
     float* out;
     float* part;          // [B][H_q][n_splits][D + 2]
     int32_t B, H_q, H_kv, G, n_splits, max_kv_len;

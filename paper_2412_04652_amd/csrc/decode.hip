@@ -56,15 +56,23 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(DecodeParams 
     const int sub = lane / LPR, sl = lane % LPR;  // row within the instruction, slice of D
     int kv_len = p.kv_len[b * p.H_kv + hk];
     kv_len = kv_len < 0 ? 0 : (kv_len > p.max_kv_len ? p.max_kv_len : kv_len);  // stay inside the slab
-    // this workgroup's slice of the key axis, a multiple of the per-iteration footprint
-    int per = (kv_len + p.n_splits - 1) / p.n_splits;
-    per = (per + kDecWaves * KPI - 1) / (kDecWaves * KPI) * (kDecWaves * KPI);
-    const int s0 = split * per;
-    const int s1 = min(s0 + per, kv_len);
+    // Fused append: the new token's k, v are row `new_row` of the stream; the lanes that meet
+    // it read it from k_new / v_new and also store it into the cache (kv_len itself is bumped
+    // by the merge kernel, after every workgroup of this launch has read it).
+    const int new_row = (p.k_new != nullptr && kv_len < p.cache_cap && kv_len < p.max_kv_len) ? kv_len : -1;
+    if (new_row >= 0) kv_len += 1;
+    // The splits of one (sequence, KV head) interleave: workgroup `split` takes the key blocks
+    // split, split + n_splits, ... of 4*KPI keys, so the workgroups of a head sweep its K and V
+    // slabs together (fewer, wider streams for the memory system than one slice per workgroup).
+    const int s0 = (split * kDecWaves + wave) * KPI;
+    const int s1 = kv_len;
+    const int t_step = p.n_splits * kDecWaves * KPI;
     const float NEG_INF = -__builtin_inff();
 
-    const char* kb = reinterpret_cast<const char*>(p.k_cache) + (int64_t)b * p.stride_b + (int64_t)hk * p.stride_head + sl * 16;
-    const char* vb = reinterpret_cast<const char*>(p.v_cache) + (int64_t)b * p.stride_b + (int64_t)hk * p.stride_head + sl * 16;
+    char* kb = reinterpret_cast<char*>(p.k_cache) + (int64_t)b * p.stride_b + (int64_t)hk * p.stride_head + sl * 16;
+    char* vb = reinterpret_cast<char*>(p.v_cache) + (int64_t)b * p.stride_b + (int64_t)hk * p.stride_head + sl * 16;
+    const char* kn = reinterpret_cast<const char*>(p.k_new) + ((size_t)(b * p.H_kv + hk) * D) * EB + sl * 16;
+    const char* vn = reinterpret_cast<const char*>(p.v_new) + ((size_t)(b * p.H_kv + hk) * D) * EB + sl * 16;
 
     for (int g0 = 0; g0 < p.G; g0 += GT) {
         float q[GT][EPL], o[GT][EPL], m[GT], l[GT];
@@ -79,7 +87,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(DecodeParams 
 #pragma unroll
             for (int e = 0; e < EPL; ++e) { q[g][e] *= p.scale_log2; o[g][e] = 0.f; }
         }
-        for (int t0 = s0 + wave * KPI; t0 < s1; t0 += kDecWaves * KPI) {
+        for (int t0 = s0; t0 < s1; t0 += t_step) {
             u32x4 kw[kDecUnroll], vw[kDecUnroll];
             bool ok[kDecUnroll];
 #pragma unroll
@@ -87,8 +95,13 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(DecodeParams 
                 const int t = t0 + u * RPW + sub;
                 ok[u] = t < s1;
                 const int tc = ok[u] ? t : s1 - 1;
-                kw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (int64_t)tc * p.stride_tok));
-                vw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (int64_t)tc * p.stride_tok));
+                const bool is_new = tc == new_row;
+                kw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(is_new ? kn : kb + (int64_t)tc * p.stride_tok));
+                vw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(is_new ? vn : vb + (int64_t)tc * p.stride_tok));
+                if (is_new && ok[u] && g0 == 0) {  // exactly one lane group of one workgroup meets the new row
+                    *reinterpret_cast<u32x4*>(kb + (int64_t)tc * p.stride_tok) = kw[u];
+                    *reinterpret_cast<u32x4*>(vb + (int64_t)tc * p.stride_tok) = vw[u];
+                }
             }
             float s[GT][kDecUnroll];
 #pragma unroll
@@ -198,6 +211,11 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p) {
         outv = od / ls;
     }
     p.out[(size_t)(b * p.H_q + hq) * D + d] = outv;
+    if (p.k_new != nullptr && d == 0 && hq % p.G == 0) {  // the fused append becomes visible to the next call
+        const int hk = hq / p.G;
+        const int len = p.kv_len[b * p.H_kv + hk];
+        if (len >= 0 && len < p.cache_cap && len < p.max_kv_len) p.kv_len[b * p.H_kv + hk] = len + 1;
+    }
 }
 
 template <typename E, int D, int GT>

@@ -87,3 +87,10 @@ class CspLayer:
         B_.csp_decode_attn(self.desc, q, self.k_cache, self.v_cache, self.cache_strides, self.kv_len,
                            self.cache_cap, o, self.ws_decode, stream)
         return o
+
+    def decode_step(self, q, k_new, v_new, stream=None, out: Optional[torch.Tensor] = None):
+        """append + attend in one call"""
+        o = self.out if out is None else out
+        B_.csp_decode_step(self.desc, q, k_new, v_new, self.k_cache, self.v_cache, self.cache_strides,
+                           self.cache_cap, self.kv_len, o, self.ws_decode, stream)
+        return o

@@ -320,6 +320,46 @@ def test_append_then_decode(gpu, oracle):
                 np.testing.assert_array_equal(kc[b, h, base[b, h] + t], case.dec_k[t, b, h])
 
 
+@pytest.mark.parametrize("dtype,D,H_q,H_kv", [("bf16", 128, 4, 4), ("bf16", 128, 14, 2), ("f32", 64, 6, 3)])
+def test_decode_step_equals_append_then_attend(gpu, oracle, dtype, D, H_q, H_kv):
+    """The fused call must leave the same cache and kv_len as csp_append_kv and return what
+    csp_decode_attn returns afterwards (and what the oracle says), also when a slab is full."""
+    U = _util()
+    from paper_2412_04652_amd.runner import CspLayer
+    rng = np.random.default_rng(D + H_q)
+    lens = [0, 5, 300, 1027, 1030]
+    B, G = len(lens), H_q // H_kv
+    mk = (lambda shape: W.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))) if dtype == "bf16" \
+        else (lambda shape: rng.standard_normal(shape, dtype=np.float32))
+    lays = [CspLayer(dtype=dtype, H_q=H_q, H_kv=H_kv, D=D, O=1, R=1, sel_group=G, cu_seqlens=list(range(B + 1)),
+                     budgets=[1029] * B, decode_cap=1029) for _ in range(2)]
+    cap = lays[0].cache_cap                     # 1030: the last sequence's slabs are full
+    kc, vc = mk((B, H_kv, cap, D)), mk((B, H_kv, cap, D))
+    for lay in lays:
+        lay.k_cache.copy_(U.to_dev(kc, dtype)); lay.v_cache.copy_(U.to_dev(vc, dtype))
+        lay.kv_len.copy_(torch.tensor(lens, dtype=torch.int32)[:, None].expand(B, H_kv))
+    for step in range(3):
+        q, kn, vn = mk((B, H_q, D)), mk((B, H_kv, D)), mk((B, H_kv, D))
+        dq, dk, dv = U.to_dev(q, dtype), U.to_dev(kn, dtype), U.to_dev(vn, dtype)
+        out_f = lays[0].decode_step(dq, dk, dv).clone()
+        lays[1].append(dk, dv)
+        out_r = lays[1].decode(dq)
+        torch.cuda.synchronize()
+        assert torch.equal(lays[0].kv_len, lays[1].kv_len)
+        assert torch.equal(lays[0].k_cache.view(torch.uint8), lays[1].k_cache.view(torch.uint8))
+        assert torch.equal(lays[0].v_cache.view(torch.uint8), lays[1].v_cache.view(torch.uint8))
+        assert torch.equal(out_f, out_r)         # same kernel, same order of operations
+        kvl = lays[0].kv_len.cpu().numpy()
+        kch, vch = U.from_dev_bits(lays[0].k_cache, dtype), U.from_dev_bits(lays[0].v_cache, dtype)
+        for b in range(B):
+            assert kvl[b, 0] == min(lens[b] + step + 1, cap)
+            for hq in range(0, H_q, max(1, H_q // 3)):
+                hk, T = hq // G, int(kvl[b, hq // G])
+                ref = oracle.decode(oracle.to_f64(q[b, hq], dtype), oracle.to_f64(kch[b, hk, :T], dtype),
+                                    oracle.to_f64(vch[b, hk, :T], dtype), 1.0)
+                U.assert_decode_close(out_f[b, hq].cpu().numpy(), ref, f"decode_step step{step} b{b} h{hq}")
+
+
 # ---------------------------------------------------------------------------
 # end to end: score -> select -> compact -> append/decode
 # ---------------------------------------------------------------------------
@@ -357,8 +397,11 @@ def _end_to_end(U, oracle, case, heads_to_check, decode_steps):
     dq = U.to_dev(case.dec_q, case.dtype)
     dk, dv = U.to_dev(case.dec_k, case.dtype), U.to_dev(case.dec_v, case.dtype)
     for t in range(decode_steps):
-        lay.append(dk[t], dv[t])
-        out = lay.decode(dq[t]).cpu().numpy()
+        if t % 2:                      # alternate the fused and the two-call form
+            out = lay.decode_step(dq[t], dk[t], dv[t]).cpu().numpy()
+        else:
+            lay.append(dk[t], dv[t])
+            out = lay.decode(dq[t]).cpu().numpy()
         for b, s in heads_to_check:
             lo, hi = int(case.cu_seqlens[b]), int(case.cu_seqlens[b + 1])
             for hq in range(s * case.sel_group, (s + 1) * case.sel_group):
