@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--budget", type=float, default=0.5, help="cache budget as a fraction of the sequence length")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--decode-steps", type=int, default=-1, help="override the decode steps per pass")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams the independent layers of the pruning phase alternate over (1 = strictly serial)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-budget", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
@@ -91,26 +93,41 @@ class Timer:
         return {k: [a.elapsed_time(b) for a, b in v] for k, v in self.pairs.items()}
 
 
-def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8):
+def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, streams=None):
     """One step: prune every layer, then the decode loop.  Event pairs bracket the
     phases; every `sample_every`-th call of each kernel family is bracketed on its own."""
+    import torch
     n_call = 0
     a, b = timer.span("prune")
     a.record()
-    for inp, lay in zip(inputs, layers):
-        sampled = (n_call % sample_every) == 0
-        n_call += 1
-        if sampled:
-            e0, e1 = timer.span("score"); e0.record()
-        lay.score(inp["q"], inp["k"], inp["mod"])
-        if sampled:
-            e1.record(); e2, e3 = timer.span("select"); e2.record()
-        lay.select(inp["mod"])
-        if sampled:
-            e3.record(); e4, e5 = timer.span("compact"); e4.record()
-        lay.compact(inp["k"], inp["v"])
-        if sampled:
-            e5.record()
+    if streams is None:
+        for inp, lay in zip(inputs, layers):
+            sampled = (n_call % sample_every) == 0
+            n_call += 1
+            if sampled:
+                e0, e1 = timer.span("score"); e0.record()
+            lay.score(inp["q"], inp["k"], inp["mod"])
+            if sampled:
+                e1.record(); e2, e3 = timer.span("select"); e2.record()
+            lay.select(inp["mod"])
+            if sampled:
+                e3.record(); e4, e5 = timer.span("compact"); e4.record()
+            lay.compact(inp["k"], inp["v"])
+            if sampled:
+                e5.record()
+    else:
+        # layers are independent: alternate them over the streams so that one layer's
+        # latency-bound selection overlaps with another layer's streaming kernels
+        main = torch.cuda.current_stream()
+        for s in streams:
+            s.wait_stream(main)
+        for li, (inp, lay) in enumerate(zip(inputs, layers)):
+            with torch.cuda.stream(streams[li % len(streams)]):
+                lay.score(inp["q"], inp["k"], inp["mod"])
+                lay.select(inp["mod"])
+                lay.compact(inp["k"], inp["v"])
+        for s in streams:
+            main.wait_stream(s)
     b.record()
     a, b = timer.span("decode")
     a.record()
@@ -127,8 +144,9 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8):
     b.record()
 
 
-def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device):
+def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_streams=1):
     import torch
+    streams = [torch.cuda.Stream(device=device) for _ in range(n_streams)] if n_streams > 1 else None
     layers, T = make_layers(cfg, inputs, budget_frac, decode_steps, device)
     g = torch.Generator(device=device); g.manual_seed(777)
     nd = 4
@@ -137,15 +155,21 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device):
                k=[torch.randn((cfg["B"], cfg["H"], cfg["D"]), generator=g, device=device).to(torch.bfloat16) for _ in range(nd)],
                v=[torch.randn((cfg["B"], cfg["H"], cfg["D"]), generator=g, device=device).to(torch.bfloat16) for _ in range(nd)])
     for _ in range(warmup):
-        run_pass(cfg, inputs, layers, dec, decode_steps, Timer())
+        run_pass(cfg, inputs, layers, dec, decode_steps, Timer(), streams=streams)
     torch.cuda.synchronize()
     timer = Timer()
     t0 = time.perf_counter()
     for _ in range(steps):
-        run_pass(cfg, inputs, layers, dec, decode_steps, timer)
+        run_pass(cfg, inputs, layers, dec, decode_steps, timer, streams=streams)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms = timer.totals_ms()
+    if streams is not None:
+        # per-call figures of the pruning kernels: one extra, untimed pass on a single stream
+        probe = Timer()
+        run_pass(cfg, inputs, layers, dec, 0, probe, sample_every=4)
+        torch.cuda.synchronize()
+        ms.update({k: v for k, v in probe.totals_ms().items() if k in ("score", "select", "compact")})
     n_layers, B, H, D, L, O = len(layers), cfg["B"], cfg["H"], cfg["D"], cfg["L"], cfg["O"]
     e = 2
     avg = lambda xs: sum(xs) / max(len(xs), 1)
@@ -256,10 +280,10 @@ def main():
     decode_steps = cfg["steps"] if args.decode_steps < 0 else args.decode_steps
     inputs = build_inputs(cfg, n_layers, device)
     torch.cuda.synchronize()
-    main_res = measure(cfg, inputs, args.budget, decode_steps, args.steps, args.warmup, device)
+    main_res = measure(cfg, inputs, args.budget, decode_steps, args.steps, args.warmup, device, args.streams)
     second = None
     if not args.no_second_budget and args.workload == "7b_16k":
-        second = measure(cfg, inputs, 0.2 if abs(args.budget - 0.5) < 1e-9 else 0.5, decode_steps, 1, 1, device)
+        second = measure(cfg, inputs, 0.2 if abs(args.budget - 0.5) < 1e-9 else 0.5, decode_steps, 1, 1, device, args.streams)
     peak_copy = copy_peak(device)
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds)
 
@@ -277,7 +301,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {n_layers} layers x B{cfg['B']} x H{cfg['H']} x L{cfg['L']} x D{cfg['D']} bf16, "
                                f"window {cfg['O']}, budget {args.budget:g}, {decode_steps} decode steps",
-                   "budget": args.budget, "layers": n_layers, "decode_steps": decode_steps},
+                   "budget": args.budget, "layers": n_layers, "decode_steps": decode_steps,
+                   "prune_streams": args.streams},
         "prune_ms_all_layers": main_res["prune_ms"],
         "prune_hbm_gbps": main_res["prune_gbps"], "prune_frac_of_peak": main_res["prune_gbps"] / HBM_PEAK_GBPS,
         "decode_attn_hbm_gbps": main_res.get("decode_gbps"),

@@ -36,7 +36,7 @@ constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
 
 // Prefetch depth (tiles in flight per wavefront) of the two passes for 2-byte elements.
 #ifndef CSP_SCORE_PF_A
-#define CSP_SCORE_PF_A 2
+#define CSP_SCORE_PF_A 1
 #endif
 #ifndef CSP_SCORE_PF_B
 #define CSP_SCORE_PF_B 1
@@ -47,6 +47,17 @@ constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
 #define CSP_SCORE_QB_LDS 0
 #endif
 constexpr bool kQbLds = CSP_SCORE_QB_LDS != 0;
+#ifndef CSP_SCORE_QA_LDS
+#define CSP_SCORE_QA_LDS 1
+#endif
+constexpr bool kQaLds = CSP_SCORE_QA_LDS != 0;
+// wavefronts per SIMD the two passes are compiled for (register budget = 512 / this)
+#ifndef CSP_SCORE_WPE_A
+#define CSP_SCORE_WPE_A 3
+#endif
+#ifndef CSP_SCORE_WPE_B
+#define CSP_SCORE_WPE_B 2
+#endif
 template <typename E> struct Prefetch;
 template <> struct Prefetch<bf16_tag> { static constexpr int A = CSP_SCORE_PF_A, B = CSP_SCORE_PF_B; };
 template <> struct Prefetch<f32_tag> { static constexpr int A = 1, B = 1; };  // 4-byte rows: 64 registers per tile
@@ -245,10 +256,10 @@ __device__ __forceinline__ void stats_tile(f32x16 (&acc)[NQB], float c, int j0, 
 // Pass A: per (sequence, query head, chunk) partial row statistics.
 // ---------------------------------------------------------------------------
 template <typename E, int D, int NQB>
-__global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_stats_kernel(ScoreParams p) {
+__global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void score_stats_kernel(ScoreParams p) {
     using G = Geom<E, D>;
-    using QF = QFrags<E, D, NQB, false>;   // bf16: query fragments in registers
-    using SM = Smem<E, D, NQB, false>;
+    using QF = QFrags<E, D, NQB, kQaLds>;
+    using SM = Smem<E, D, NQB, kQaLds>;
     extern __shared__ __align__(16) char smem[];
     const int chunk = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
@@ -268,10 +279,17 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_stats_kernel
     const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
+#ifdef CSP_SCORE_SLAB
     const int cpw = p.chunk_keys / kWaves;
     const int jb = c0 + wave * cpw;
     const int je = min(jb + cpw, L);
     const int ntiles = je > jb ? (je - jb + kTile - 1) / kTile : 0;
+#else
+    // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
+    // so a workgroup sweeps its chunk as one stream
+    const int ntc = (min(c0 + p.chunk_keys, L) - c0 + kTile - 1) / kTile;
+    const int ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
+#endif
 
     float m_run[NQB], l_run[NQB];
     int pos_q[NQB];  // absolute position of this lane's query in block nb
@@ -291,11 +309,19 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_stats_kernel
     // Tiles are visited in a rotated order (tile (t + rot) mod ntiles at step t) with a
     // different rotation per wavefront and workgroup: all key runs are aligned to large powers
     // of two, and wavefronts walking them in lockstep would hit the same memory channels.
+#ifdef CSP_SCORE_SLAB
     const int rot = ntiles > 0 ? (int)((wave * 3u + chunk * 5u + hq * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? jb + (tt < ntiles ? tt : tt - ntiles) * kTile : L - 1;
     };
+#else
+    const int rot = ntiles > 0 ? (int)((chunk * 5u + hq * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
+        const int tt = t + rot;
+        return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
+    };
+#endif
     // the key stream starts first; the queries (L2-resident, small) follow
     if (ntiles > 0) {
 #pragma unroll
@@ -408,7 +434,7 @@ __device__ __forceinline__ void colsum_tile(const f32x16 (&acc)[NQB], float c, c
 // Pass B: per (sequence, selection group, chunk) column sums.
 // ---------------------------------------------------------------------------
 template <typename E, int D, int NQB>
-__global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kernel(ScoreParams p) {
+__global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void score_colsum_kernel(ScoreParams p) {
     using G = Geom<E, D>;
     using QF = QFrags<E, D, NQB, kQbLds>;
     using SM = Smem<E, D, NQB, kQbLds>;
@@ -448,21 +474,36 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kerne
         for (int v = 0; v < 16; ++v)
             if (wq[mb * 32 + acc_row(v, half)] == 0) text_bits[mb / 2] |= 1u << ((mb & 1) * 16 + v);
 
+#ifdef CSP_SCORE_SLAB
     const int cpw = p.chunk_keys / kWaves;
     const int jb = c0 + wave * cpw;
     const int je = min(jb + cpw, L);
     const int ntiles = je > jb ? (je - jb + kTile - 1) / kTile : 0;
+#else
+    // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
+    // so a workgroup sweeps its chunk as one stream
+    const int ntc = (min(c0 + p.chunk_keys, L) - c0 + kTile - 1) / kTile;
+    const int ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
+#endif
     const int rank_end = L - R;                                   // keys >= rank_end are not ranked
     const int mask_from = min(rank_end, p.causal ? L - O : L);    // below: no masking needed
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
     constexpr int PF = Prefetch<E>::B;
     // same rotated visiting order as pass A (the two passes need not agree)
+#ifdef CSP_SCORE_SLAB
     const int rot = ntiles > 0 ? (int)((wave * 3u + chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? jb + (tt < ntiles ? tt : tt - ntiles) * kTile : L - 1;
     };
+#else
+    const int rot = ntiles > 0 ? (int)((chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
+        const int tt = t + rot;
+        return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
+    };
+#endif
     auto load_mod = [&](int j0) -> uint8_t {  // modality of key j0 + lane%32, fetched with its tile
         const int j = j0 + (lane & 31);
         return p.modality[seq0 + (j < L ? j : L - 1)];
@@ -586,7 +627,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? 2 : 1) void score_colsum_kerne
 
 template <typename E, int D, int NQB>
 hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
-    const size_t smem_a = Smem<E, D, NQB, false>::total, smem_b = Smem<E, D, NQB, kQbLds>::total;
+    const size_t smem_a = Smem<E, D, NQB, kQaLds>::total, smem_b = Smem<E, D, NQB, kQbLds>::total;
     auto ka = score_stats_kernel<E, D, NQB>;
     auto kb = score_colsum_kernel<E, D, NQB>;
     if (smem_a > 64 * 1024) {
