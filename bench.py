@@ -136,11 +136,16 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, stre
         for li, lay in enumerate(layers):
             sampled = (n_call % sample_every) == 0
             n_call += 1
+            dq, dk, dv = dec["q"][t % dec["n"]], dec["k"][t % dec["n"]], dec["v"][t % dec["n"]]
             if sampled:
-                e0, e1 = timer.span("decode_call"); e0.record()
-            lay.decode_step(dec["q"][t % dec["n"]], dec["k"][t % dec["n"]], dec["v"][t % dec["n"]])  # append + attend
-            if sampled:
+                # the same two launches as decode_step, issued one by one so that the events
+                # bracket the streaming kernel alone
+                e0, e1 = timer.span("decode_split"); e0.record()
+                lay.decode_step_phase(1, dq, dk, dv)
                 e1.record()
+                lay.decode_step_phase(2, dq, dk, dv)
+            else:
+                lay.decode_step(dq, dk, dv)  # append + attend
     b.record()
 
 
@@ -193,10 +198,10 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
         })
     if decode_steps > 0:
         dec_ms = avg(ms["decode"])
-        call_ms = avg(ms["decode_call"])
+        call_ms = avg(ms["decode_split"])
         res.update(decode_ms_per_token=dec_ms / decode_steps,
                    decode_gbps=by_decode * n_layers * decode_steps / (dec_ms * 1e-3) / 1e9)
-        res["kernels"]["decode_step(split+merge)"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
+        res["kernels"]["decode_split"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
     del layers
     torch.cuda.empty_cache()
     return res
@@ -291,8 +296,17 @@ def main():
     kern = main_res["kernels"]
     step_share = {k: v["ms"] * (n_layers * (decode_steps if k.startswith("decode") else 1)) for k, v in kern.items()}
     dom = max(step_share, key=step_share.get)
+    # measured HBM traffic per launch of that kernel (rocprofv3 --pmc, see profiles/), if recorded
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            rec = json.load(f).get(f"{args.workload}@{args.budget:g}", {}).get(dom.split("(")[0])
+        if rec:
+            traffic = rec["fetch_bytes"] + rec["write_bytes"]
+    except (OSError, ValueError, KeyError):
+        traffic = None
     roof = dict(bound="hbm", kernel=dom, achieved=kern[dom]["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                frac=kern[dom]["gbps"] / HBM_PEAK_GBPS, traffic=None,
+                frac=kern[dom]["gbps"] / HBM_PEAK_GBPS, traffic=traffic,
                 algorithmic_bytes_per_launch=kern[dom]["bytes"], avg_launch_ms=kern[dom]["ms"])
     out = {
         "metric": "pruned KV tokens/sec (score+select+compact) and decode attn HBM GB/s, 1 GPU",

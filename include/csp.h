@@ -193,6 +193,19 @@ int csp_decode_step(const csp_desc* desc, const void* q, const void* k_new, cons
                     void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * csp_decode_step_phase — the two launches of csp_decode_step one at a time,
+ * for callers that time or schedule them apart: phase 1 streams the cache
+ * (split-KV partials into ws, new token stored), phase 2 merges the partials,
+ * applies the n of Eq. "n-softmax" and increments kv_len.  Phase 1 followed by
+ * phase 2 with the same arguments on the same stream is exactly
+ * csp_decode_step.  Any other phase value is CSP_EINVAL.
+ * ---------------------------------------------------------------------- */
+int csp_decode_step_phase(const csp_desc* desc, int32_t phase, const void* q, const void* k_new,
+                          const void* v_new, void* k_cache, void* v_cache, int64_t cache_stride_b,
+                          int64_t cache_stride_head, int64_t cache_stride_tok, int32_t cache_cap,
+                          int32_t* kv_len, float* out, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * csp_append_kv — the KV-cache append of Section "Preliminary": writes the new
  * token's key and value (device [B][H_kv][D]) at row kv_len[b][h] of the
  * pruned cache and increments kv_len[b][h].  cache_cap is the number of rows

@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "csp_score_workspace_bytes", "csp_score",
     "csp_select_workspace_bytes", "csp_select",
     "csp_compact",
-    "csp_decode_workspace_bytes", "csp_decode_attn", "csp_decode_step",
+    "csp_decode_workspace_bytes", "csp_decode_attn", "csp_decode_step", "csp_decode_step_phase",
     "csp_append_kv",
 ]
 
@@ -65,6 +65,7 @@ def load_library():
         L.csp_compact.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, vp, vp]; L.csp_compact.restype = C.c_int
         L.csp_decode_attn.argtypes = [dp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, sz, vp]; L.csp_decode_attn.restype = C.c_int
         L.csp_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]; L.csp_decode_step.restype = C.c_int
+        L.csp_decode_step_phase.argtypes = [dp, i32, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]; L.csp_decode_step_phase.restype = C.c_int
         L.csp_append_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]; L.csp_append_kv.restype = C.c_int
         _lib = L
     return _lib
@@ -185,3 +186,11 @@ def csp_decode_step(desc: Desc, q, k_new, v_new, k_cache, v_cache, cache_strides
                                           int(cache_strides[0]), int(cache_strides[1]), int(cache_strides[2]),
                                           int(cache_cap), _ptr(kv_len), _ptr(out), _ptr(ws), _nbytes(ws),
                                           _stream(stream)), "csp_decode_step")
+
+
+def csp_decode_step_phase(desc: Desc, phase: int, q, k_new, v_new, k_cache, v_cache, cache_strides, cache_cap: int,
+                          kv_len, out, ws, stream=None) -> None:
+    _check(load_library().csp_decode_step_phase(desc.ref(), int(phase), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache),
+                                                _ptr(v_cache), int(cache_strides[0]), int(cache_strides[1]),
+                                                int(cache_strides[2]), int(cache_cap), _ptr(kv_len), _ptr(out), _ptr(ws),
+                                                _nbytes(ws), _stream(stream)), "csp_decode_step_phase")

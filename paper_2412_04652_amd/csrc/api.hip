@@ -180,7 +180,7 @@ size_t csp_decode_workspace_bytes(const csp_desc* d, int32_t max_kv_len) {
 static int decode_common(const csp_desc* d, const void* q, const void* k_new, const void* v_new,
                          void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
                          int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, int32_t max_kv_len,
-                         float* out, void* ws, size_t ws_bytes, void* stream) {
+                         float* out, void* ws, size_t ws_bytes, void* stream, int phases = 3) {
     Checked c;
     int rc = check_desc(d, false, &c);
     if (rc != CSP_OK) return rc;
@@ -195,6 +195,7 @@ static int decode_common(const csp_desc* d, const void* q, const void* k_new, co
     std::memset(&p, 0, sizeof(p));
     p.q = q; p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_len = kv_len; p.out = out;
     p.cache_cap = cache_cap;
+    p.phases = phases;
     p.part = static_cast<float*>(ws);
     p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.G = c.G;
     p.n_splits = decode_num_splits(d->B, d->H_kv, max_kv_len);
@@ -221,6 +222,15 @@ int csp_decode_step(const csp_desc* d, const void* q, const void* k_new, const v
     if (!k_new || !v_new) return CSP_EINVAL;
     return decode_common(d, q, k_new, v_new, k_cache, v_cache, cache_stride_b, cache_stride_head, cache_stride_tok,
                          cache_cap, kv_len, cache_cap, out, ws, ws_bytes, stream);
+}
+
+int csp_decode_step_phase(const csp_desc* d, int32_t phase, const void* q, const void* k_new, const void* v_new,
+                          void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                          int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, float* out, void* ws,
+                          size_t ws_bytes, void* stream) {
+    if (!k_new || !v_new || (phase != 1 && phase != 2)) return CSP_EINVAL;
+    return decode_common(d, q, k_new, v_new, k_cache, v_cache, cache_stride_b, cache_stride_head, cache_stride_tok,
+                         cache_cap, kv_len, cache_cap, out, ws, ws_bytes, stream, phase);
 }
 
 int csp_append_kv(const csp_desc* d, const void* k_new, const void* v_new, void* k_cache,

@@ -91,6 +91,7 @@ struct DecodeParams {
     void* v_cache;
     int32_t* kv_len;
     int32_t cache_cap;
+    int32_t phases;       // bit 0: split kernel, bit 1: merge kernel
     float* out;
     float* part;          // [B][H_q][n_splits][D + 2]
     int32_t B, H_q, H_kv, G, n_splits, max_kv_len;

@@ -220,10 +220,12 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p) {
 
 template <typename E, int D, int GT>
 hipError_t launch_gt(const DecodeParams& p, hipStream_t s) {
-    hipLaunchKernelGGL((decode_split_kernel<E, D, GT>), dim3(p.n_splits, p.H_kv, p.B), dim3(kDecThreads), 0, s, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(p.H_q, p.B), dim3(D), 0, s, p);
+    if (p.phases & 1) {
+        hipLaunchKernelGGL((decode_split_kernel<E, D, GT>), dim3(p.n_splits, p.H_kv, p.B), dim3(kDecThreads), 0, s, p);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (p.phases & 2) hipLaunchKernelGGL((decode_merge_kernel<D>), dim3(p.H_q, p.B), dim3(D), 0, s, p);
     return hipGetLastError();
 }
 

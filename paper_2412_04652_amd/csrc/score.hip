@@ -23,8 +23,6 @@
 // between the load layout and the MFMA operand layout, no workgroup barrier
 // in the loop.  All exponentials are base 2 with log2(e)/sqrt(D) folded into
 // one FMA per element.
-#include <cstdlib>
-
 #include "csp_internal.h"
 
 namespace csp {
@@ -279,17 +277,10 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
-#ifdef CSP_SCORE_SLAB
-    const int cpw = p.chunk_keys / kWaves;
-    const int jb = c0 + wave * cpw;
-    const int je = min(jb + cpw, L);
-    const int ntiles = je > jb ? (je - jb + kTile - 1) / kTile : 0;
-#else
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
     // so a workgroup sweeps its chunk as one stream
     const int ntc = (min(c0 + p.chunk_keys, L) - c0 + kTile - 1) / kTile;
     const int ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
-#endif
 
     float m_run[NQB], l_run[NQB];
     int pos_q[NQB];  // absolute position of this lane's query in block nb
@@ -309,19 +300,11 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     // Tiles are visited in a rotated order (tile (t + rot) mod ntiles at step t) with a
     // different rotation per wavefront and workgroup: all key runs are aligned to large powers
     // of two, and wavefronts walking them in lockstep would hit the same memory channels.
-#ifdef CSP_SCORE_SLAB
-    const int rot = ntiles > 0 ? (int)((wave * 3u + chunk * 5u + hq * 7u + b * 11u) % (unsigned)ntiles) : 0;
-    auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
-        const int tt = t + rot;
-        return t < ntiles ? jb + (tt < ntiles ? tt : tt - ntiles) * kTile : L - 1;
-    };
-#else
     const int rot = ntiles > 0 ? (int)((chunk * 5u + hq * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
     };
-#endif
     // the key stream starts first; the queries (L2-resident, small) follow
     if (ntiles > 0) {
 #pragma unroll
@@ -342,14 +325,8 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
                 store_tile<E, D>(st[u], tile, lane);
                 wave_lds_sync();
             }
-#ifndef CSP_DBG_NO_LOAD
             load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
-#endif
             if (!live) continue;
-#ifdef CSP_DBG_NO_COMPUTE
-            l_run[0] += __uint_as_float(st[u][0][0]) + *reinterpret_cast<const float*>(tile + lane * 4);
-            continue;
-#endif
 
             f32x16 acc[NQB];
 #pragma unroll
@@ -474,36 +451,21 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
         for (int v = 0; v < 16; ++v)
             if (wq[mb * 32 + acc_row(v, half)] == 0) text_bits[mb / 2] |= 1u << ((mb & 1) * 16 + v);
 
-#ifdef CSP_SCORE_SLAB
-    const int cpw = p.chunk_keys / kWaves;
-    const int jb = c0 + wave * cpw;
-    const int je = min(jb + cpw, L);
-    const int ntiles = je > jb ? (je - jb + kTile - 1) / kTile : 0;
-#else
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
     // so a workgroup sweeps its chunk as one stream
     const int ntc = (min(c0 + p.chunk_keys, L) - c0 + kTile - 1) / kTile;
     const int ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
-#endif
     const int rank_end = L - R;                                   // keys >= rank_end are not ranked
     const int mask_from = min(rank_end, p.causal ? L - O : L);    // below: no masking needed
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
     constexpr int PF = Prefetch<E>::B;
     // same rotated visiting order as pass A (the two passes need not agree)
-#ifdef CSP_SCORE_SLAB
-    const int rot = ntiles > 0 ? (int)((wave * 3u + chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
-    auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
-        const int tt = t + rot;
-        return t < ntiles ? jb + (tt < ntiles ? tt : tt - ntiles) * kTile : L - 1;
-    };
-#else
     const int rot = ntiles > 0 ? (int)((chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
     };
-#endif
     auto load_mod = [&](int j0) -> uint8_t {  // modality of key j0 + lane%32, fetched with its tile
         const int j = j0 + (lane & 31);
         return p.modality[seq0 + (j < L ? j : L - 1)];
@@ -565,16 +527,9 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
                 }
                 const bool key_text = kmod[u] == 0;
                 // one tile of loads per iteration on every path (see the ring in pass A)
-#ifndef CSP_DBG_NO_LOAD
                 load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
                 kmod[u] = load_mod(tile_key(t + PF));
-#endif
                 if (!live) continue;
-#ifdef CSP_DBG_NO_COMPUTE
-                if (half == 0 && j0 + (lane & 31) < L)
-                    p.score_self[(size_t)sg * p.total_tokens + seq0 + j0 + (lane & 31)] = __uint_as_float(st[u][0][0]) + *reinterpret_cast<const float*>(tile + lane * 4) + (key_text ? 1.f : 0.f);
-                continue;
-#endif
 
                 // the accumulator starts at -lse_i/c, so that 2^(c*acc) is the normalised weight
                 f32x16 acc[NQB];
@@ -658,9 +613,6 @@ hipError_t launch_nqb(const ScoreParams& p, hipStream_t s) {
 }  // namespace
 
 int score_chunk_keys(int B, int H_q, int max_seqlen) {
-#ifdef CSP_DBG_CHUNK_ENV
-    if (const char* e = getenv("CSP_SCORE_CHUNK")) return atoi(e);
-#endif
     // largest chunk that still gives every compute unit about four workgroups (two resident at a
     // time): long chunks amortise the per-head set-up of a workgroup
     int ck = 4096;

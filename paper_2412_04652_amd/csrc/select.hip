@@ -15,8 +15,8 @@
 // threshold, or equal and among the first few equals" is a chain of wave
 // ballots and popcounts in key order plus two block-wide exchanges of
 // per-wavefront totals per super-block; the kept positions come out ascending,
-// with the lower-index-first tie rule, and without atomics on the output.  With a single-modality window every key belongs to exactly one
-// region: one bit pattern per key stays in registers for all passes when the
+// with the lower-index-first tie rule, and without atomics on the output.  With
+// a single-modality window every key belongs to exactly one region: one bit pattern per key stays in registers for all passes when the
 // sequence fits one super-block.
 #include "csp_internal.h"
 
@@ -27,13 +27,6 @@ constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kBins = 2048;
 constexpr uint32_t kNone = 0xffffffffu;  // "not a candidate": no finite non-negative float
-
-#ifdef CSP_SEL_TRACE
-__device__ long long g_sel_trace[32];
-#define SEL_STAMP(k) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0) g_sel_trace[k] = wall_clock64(); } while (0)
-#else
-#define SEL_STAMP(k) do {} while (0)
-#endif
 
 struct SelShared {
     uint32_t hist[2][kBins];
@@ -126,10 +119,7 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
             return (cr == (r == 1)) ? ka[i] : kNone;
         }
     };
-
-    SEL_STAMP(1);
     if (CACHED) load_keys(0);
-    SEL_STAMP(2);
 
     // ---- radix select, both regions at once ---------------------------------
     uint32_t prefix[2] = {0u, 0u};   // threshold bits found so far (high part)
@@ -142,10 +132,8 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         const int nbits = pass == 2 ? 10 : 11;
         const int prev_shift = pass == 1 ? 21 : 10;  // bits above the current digit
         const uint32_t dmask = (1u << nbits) - 1u;
-        SEL_STAMP(3 + pass * 4);
         for (int i = tid; i < 2 * kBins; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
         __syncthreads();
-        SEL_STAMP(4 + pass * 4);
 #pragma unroll 1
         for (int sb = 0; sb < n_super; ++sb) {
             if (!CACHED) load_keys(sb);
@@ -167,7 +155,6 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
             }
         }
         __syncthreads();
-        SEL_STAMP(5 + pass * 4);
         // thread t owns bins hi = nb-1-2t and lo = hi-1 (descending order over threads)
         const int nb = 1 << nbits;
         const int hi = nb - 1 - 2 * tid;
@@ -207,7 +194,6 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         }
         __syncthreads();
     }
-    SEL_STAMP(15);
     uint32_t th_bits[2], th_eq[2];  // K-th largest pattern of the region; equals still to keep
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
@@ -287,7 +273,6 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         base_out += (uint32_t)all;
         n_both += (uint32_t)(all >> 32);
     }
-    SEL_STAMP(16);
     for (int j = (int)base_out + tid; j < c.kept_cap; j += kSelThreads) c.out[j] = -1;
     if (tid == 0) { c.cnt[0] = (int32_t)base_out; c.cnt[1] = K_s; c.cnt[2] = K_c; c.cnt[3] = (int32_t)n_both; }
 }
@@ -295,7 +280,6 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
 template <int ITEMS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     __shared__ SelShared sh;
-    SEL_STAMP(0);
     const int sg = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x;
     const int seq0 = p.cu[b];
@@ -335,10 +319,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
 }
 
 }  // namespace
-
-#ifdef CSP_SEL_TRACE
-extern "C" int csp_debug_sel_trace(long long* out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_sel_trace), sizeof(long long) * 32); }
-#endif
 
 hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s) {
     const dim3 grid(p.H_sel, p.B), block(kSelThreads);

@@ -94,3 +94,10 @@ class CspLayer:
         B_.csp_decode_step(self.desc, q, k_new, v_new, self.k_cache, self.v_cache, self.cache_strides,
                            self.cache_cap, self.kv_len, o, self.ws_decode, stream)
         return o
+
+    def decode_step_phase(self, phase, q, k_new, v_new, stream=None, out: Optional[torch.Tensor] = None):
+        """one of the two launches of decode_step (1: stream the cache, 2: merge)"""
+        o = self.out if out is None else out
+        B_.csp_decode_step_phase(self.desc, phase, q, k_new, v_new, self.k_cache, self.v_cache, self.cache_strides,
+                                 self.cache_cap, self.kv_len, o, self.ws_decode, stream)
+        return o

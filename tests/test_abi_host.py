@@ -97,6 +97,8 @@ def test_null_pointers_and_workspace(P):
     assert L.csp_compact(d.ref(), FAKE, FAKE, FAKE, 2048, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 64, None, None) == -1
     assert L.csp_decode_attn(d.ref(), FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, FAKE, 2064, FAKE, None, 0, None) == -3
     assert L.csp_decode_attn(d.ref(), FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, FAKE, 0, FAKE, FAKE, 1 << 30, None) == -1
+    assert L.csp_decode_step_phase(d.ref(), 3, FAKE, FAKE, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, 2064, FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert L.csp_decode_step(d.ref(), FAKE, None, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, 2064, FAKE, FAKE, FAKE, 1 << 30, None) == -1
     assert L.csp_append_kv(d.ref(), FAKE, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, 0, FAKE, None) == -1
 
 

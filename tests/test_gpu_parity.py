@@ -332,7 +332,7 @@ def test_decode_step_equals_append_then_attend(gpu, oracle, dtype, D, H_q, H_kv)
     mk = (lambda shape: W.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32))) if dtype == "bf16" \
         else (lambda shape: rng.standard_normal(shape, dtype=np.float32))
     lays = [CspLayer(dtype=dtype, H_q=H_q, H_kv=H_kv, D=D, O=1, R=1, sel_group=G, cu_seqlens=list(range(B + 1)),
-                     budgets=[1029] * B, decode_cap=1029) for _ in range(2)]
+                     budgets=[1029] * B, decode_cap=1029) for _ in range(3)]
     cap = lays[0].cache_cap                     # 1030: the last sequence's slabs are full
     kc, vc = mk((B, H_kv, cap, D)), mk((B, H_kv, cap, D))
     for lay in lays:
@@ -344,7 +344,11 @@ def test_decode_step_equals_append_then_attend(gpu, oracle, dtype, D, H_q, H_kv)
         out_f = lays[0].decode_step(dq, dk, dv).clone()
         lays[1].append(dk, dv)
         out_r = lays[1].decode(dq)
+        lays[2].decode_step_phase(1, dq, dk, dv)           # the two launches issued one by one
+        out_p = lays[2].decode_step_phase(2, dq, dk, dv)
         torch.cuda.synchronize()
+        assert torch.equal(out_p, out_f) and torch.equal(lays[2].kv_len, lays[0].kv_len)
+        assert torch.equal(lays[2].k_cache.view(torch.uint8), lays[0].k_cache.view(torch.uint8))
         assert torch.equal(lays[0].kv_len, lays[1].kv_len)
         assert torch.equal(lays[0].k_cache.view(torch.uint8), lays[1].k_cache.view(torch.uint8))
         assert torch.equal(lays[0].v_cache.view(torch.uint8), lays[1].v_cache.view(torch.uint8))
