@@ -16,8 +16,9 @@
 // ballots and popcounts in key order plus two block-wide exchanges of
 // per-wavefront totals per super-block; the kept positions come out ascending,
 // with the lower-index-first tie rule, and without atomics on the output.  With
-// a single-modality window every key belongs to exactly one region: one bit pattern per key stays in registers for all passes when the
-// sequence fits one super-block.
+// a single-modality window every key belongs to exactly one region: one bit
+// pattern per key stays in registers for all passes when the sequence fits one
+// super-block.
 #include "csp_internal.h"
 
 namespace csp {
