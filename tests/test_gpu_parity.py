@@ -464,6 +464,61 @@ def test_end_to_end_mixed_window_counts(gpu, oracle):
         assert int(dc.layer.kv_len[0, h]) == n
 
 
+EDGE_CASES = {
+    # name: make_case keyword overrides (base: bf16, 2 heads, D=128, O=R=8)
+    "len_9": dict(layouts=[[(1, 3), (0, 6)]], budgets=[6], O=4, R=2),
+    "len_32_exact_tile": dict(layouts=[[(0, 10), (1, 14), (0, 8)]], budgets=[20]),
+    "len_33_one_past_a_tile": dict(layouts=[[(0, 10), (1, 15), (0, 8)]], budgets=[20]),
+    "one_head": dict(H_q=1, H_kv=1, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[100]),
+    "d64_window_128": dict(D=64, O=128, R=128, layouts=[[(0, 100), (1, 500), (0, 200)]], budgets=[400]),
+    "f32_d128": dict(dtype="f32", layouts=[[(0, 90), (1, 200), (0, 43)]], budgets=[150]),
+    "only_recent_kept": dict(layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[8]),
+    "all_cross": dict(cross_ratio=1.0, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[108]),
+    "all_self": dict(cross_ratio=0.0, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[108]),
+    "ratio_0p9": dict(cross_ratio=0.9, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[108]),
+    "text_spills_into_visual": dict(layouts=[[(0, 5), (1, 400), (0, 12)]], budgets=[300]),
+    "visual_spills_into_text": dict(layouts=[[(0, 300), (1, 7), (0, 100)]], budgets=[300]),
+    "no_visual_tokens": dict(layouts=[[(0, 300)]], budgets=[100]),
+    "n_score_1": dict(n_score=1.0, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[100]),
+    "one_index_set_per_layer": dict(H_q=4, H_kv=4, sel_group=4, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[100]),
+    "identity_and_pruned_in_one_batch": dict(layouts=[[(0, 40), (1, 50), (0, 20)], [(0, 200), (1, 300), (0, 50)], [(0, 64)],
+                                                      [(1, 90), (0, 38)]], budgets=[110, 200, 100, 128]),
+    "n_decode_0": dict(n_decode=0.0, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[100]),
+    "n_decode_3": dict(n_decode=3.0, layouts=[[(0, 100), (1, 150), (0, 30)]], budgets=[100]),
+}
+
+
+@pytest.mark.parametrize("name", list(EDGE_CASES))
+def test_end_to_end_edge_cases(gpu, oracle, name):
+    U = _util()
+    kw = dict(dtype="bf16", H_q=2, H_kv=2, D=128, O=8, R=8, seed=21, decode_steps=2)
+    kw.update(EDGE_CASES[name])
+    case = W.make_case(name, **kw)
+    _say(f"[e2e-edge] {name} lens={np.diff(case.cu_seqlens).tolist()} budgets={case.budget_T.tolist()}")
+    H_sel = case.H_q // case.sel_group
+    _end_to_end(U, oracle, case, [(b, s) for b in range(case.B) for s in range(H_sel)], 2)
+
+
+def test_compact_token_major_input(gpu, oracle):
+    """K and V stored [tokens, H_kv, D]: same pruned cache as from the head-major layout."""
+    U = _util()
+    from paper_2412_04652_amd.runner import CspLayer
+    case = W.make_case("tm", dtype="bf16", H_q=4, H_kv=4, D=128, O=16, R=16,
+                       layouts=[[(0, 100), (1, 300), (0, 60)], [(1, 200), (0, 77)]], budgets=[200, 100], seed=5)
+    dc = U.DeviceCase(case)
+    dc.layer.prune(dc.q_win, dc.k, dc.v, dc.modality)
+    k_tm, v_tm = dc.k.permute(1, 0, 2).contiguous(), dc.v.permute(1, 0, 2).contiguous()
+    lay = CspLayer(dtype="bf16", H_q=4, H_kv=4, D=128, O=16, R=16, cu_seqlens=case.cu_seqlens.tolist(),
+                   budgets=case.budget_T.tolist(), k_strides=(4 * 128, 128), v_strides=(4 * 128, 128))
+    lay.prune(dc.q_win, k_tm, v_tm, dc.modality)
+    torch.cuda.synchronize()
+    assert torch.equal(lay.kept_idx, dc.layer.kept_idx) and torch.equal(lay.kv_len, dc.layer.kv_len)
+    for b in range(2):
+        n = int(lay.kv_len[b, 0])
+        assert torch.equal(lay.k_cache[b, :, :n].view(torch.int16), dc.layer.k_cache[b, :, :n].view(torch.int16))
+        assert torch.equal(lay.v_cache[b, :, :n].view(torch.int16), dc.layer.v_cache[b, :, :n].view(torch.int16))
+
+
 def test_full_budget_identity_and_full_attention(gpu, oracle):
     """T >= L: pruning is the identity and, with n = 0, decode is textbook
     attention over the whole cache."""
