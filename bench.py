@@ -47,6 +47,10 @@ def parse():
                     help="HIP streams the independent layers of the pruning phase alternate over (1 = strictly serial)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-second-budget", action="store_true")
+    ap.add_argument("--sel-group", type=int, default=1,
+                    help="query heads whose scores are summed into one index set (1 = per head, H = one set per layer)")
+    ap.add_argument("--no-head-averaged", action="store_true",
+                    help="skip the extra pass with one index set per layer (scores summed over all heads)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -67,11 +71,12 @@ def build_inputs(cfg, n_layers, device):
     return layers
 
 
-def make_layers(cfg, inputs, budget_frac, decode_steps, device):
+def make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group=1):
     from paper_2412_04652_amd.runner import CspLayer
     T = int(cfg["L"] * budget_frac)
     return [CspLayer(dtype="bf16", H_q=cfg["H"], H_kv=cfg["H"], D=cfg["D"], O=cfg["O"], R=cfg["O"],
-                     cu_seqlens=inp["cu"], budgets=[T] * cfg["B"], decode_cap=decode_steps, device=device)
+                     cu_seqlens=inp["cu"], budgets=[T] * cfg["B"], decode_cap=decode_steps, device=device,
+                     sel_group=sel_group)
             for inp in inputs], T
 
 
@@ -149,10 +154,10 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, stre
     b.record()
 
 
-def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_streams=1):
+def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_streams=1, sel_group=1):
     import torch
     streams = [torch.cuda.Stream(device=device) for _ in range(n_streams)] if n_streams > 1 else None
-    layers, T = make_layers(cfg, inputs, budget_frac, decode_steps, device)
+    layers, T = make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group)
     g = torch.Generator(device=device); g.manual_seed(777)
     nd = 4
     dec = dict(n=nd,
@@ -177,16 +182,17 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
         ms.update({k: v for k, v in probe.totals_ms().items() if k in ("score", "select", "compact")})
     n_layers, B, H, D, L, O = len(layers), cfg["B"], cfg["H"], cfg["D"], cfg["L"], cfg["O"]
     e = 2
+    Hs = H // sel_group                           # index sets per sequence
     avg = lambda xs: sum(xs) / max(len(xs), 1)
     # algorithmic bytes per launch (one layer)
-    by_score = B * (H * L * D * e + H * O * D * e + L + 2 * H * (L - O) * 4)
-    by_select = B * (2 * H * (L - O) * 4 + H * T * 4)
-    by_compact = B * (4 * H * T * D * e + H * T * 4)
+    by_score = B * (H * L * D * e + H * O * D * e + L + 2 * Hs * (L - O) * 4)
+    by_select = B * (2 * Hs * (L - O) * 4 + Hs * T * 4)
+    by_compact = B * (4 * H * T * D * e + Hs * T * 4)
     kv_mean = T + (decode_steps + 1) / 2.0
     by_decode = B * (2 * H * kv_mean * D * e + H * D * (e + 4))
     prune_ms = avg(ms["prune"])
     res = dict(
-        budget=budget_frac, T=T, layers=n_layers,
+        budget=budget_frac, T=T, layers=n_layers, sel_group=sel_group,
         prune_ms=prune_ms,
         tokens_per_s=n_layers * B * L / (prune_ms * 1e-3),
         prune_gbps=n_layers * (by_score + by_select + by_compact) / (prune_ms * 1e-3) / 1e9,
@@ -285,10 +291,15 @@ def main():
     decode_steps = cfg["steps"] if args.decode_steps < 0 else args.decode_steps
     inputs = build_inputs(cfg, n_layers, device)
     torch.cuda.synchronize()
-    main_res = measure(cfg, inputs, args.budget, decode_steps, args.steps, args.warmup, device, args.streams)
-    second = None
+    main_res = measure(cfg, inputs, args.budget, decode_steps, args.steps, args.warmup, device, args.streams,
+                       args.sel_group)
+    second = head_avg = None
     if not args.no_second_budget and args.workload == "7b_16k":
-        second = measure(cfg, inputs, 0.2 if abs(args.budget - 0.5) < 1e-9 else 0.5, decode_steps, 1, 1, device, args.streams)
+        second = measure(cfg, inputs, 0.2 if abs(args.budget - 0.5) < 1e-9 else 0.5, decode_steps, 1, 1, device, args.streams,
+                         args.sel_group)
+    if not args.no_head_averaged and args.workload == "7b_16k" and args.sel_group == 1:
+        # the paper-literal head axis: scores summed over all heads, one index set per layer and sequence
+        head_avg = measure(cfg, inputs, args.budget, 0, 1, 1, device, args.streams, cfg["H"])
     peak_copy = copy_peak(device)
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds)
 
@@ -315,7 +326,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {n_layers} layers x B{cfg['B']} x H{cfg['H']} x L{cfg['L']} x D{cfg['D']} bf16, "
                                f"window {cfg['O']}, budget {args.budget:g}, {decode_steps} decode steps",
-                   "budget": args.budget, "layers": n_layers, "decode_steps": decode_steps,
+                   "budget": args.budget, "layers": n_layers, "decode_steps": decode_steps, "sel_group": args.sel_group,
                    "prune_streams": args.streams},
         "prune_ms_all_layers": main_res["prune_ms"],
         "prune_hbm_gbps": main_res["prune_gbps"], "prune_frac_of_peak": main_res["prune_gbps"] / HBM_PEAK_GBPS,
@@ -331,6 +342,9 @@ def main():
         out["second_budget"] = {k: second[k] for k in ("budget", "T", "prune_ms", "tokens_per_s", "prune_gbps",
                                                        "decode_gbps", "decode_ms_per_token") if k in second}
         out["second_budget"]["kernels"] = second["kernels"]
+    if head_avg is not None:
+        out["head_averaged"] = {k: head_avg[k] for k in ("budget", "T", "sel_group", "prune_ms", "tokens_per_s", "prune_gbps")}
+        out["head_averaged"]["kernels"] = head_avg["kernels"]
     print(json.dumps(out), flush=True)
 
 

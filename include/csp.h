@@ -105,6 +105,9 @@ const char* csp_version(void);
  *   modality  device uint8[total_tokens], 0 = text, 1 = visual
  *   score_*   device float [H_sel][total_tokens]
  *   ws        device scratch of csp_score_workspace_bytes(desc) bytes, 16-byte aligned
+ *             (softmax statistics per chunk; for a large selection group that is
+ *             summed in several slices, also one partial score array per slice,
+ *             added in slice order: the result does not depend on scheduling)
  * Requires O <= L_b and R <= L_b for every sequence (CSP_EINVAL otherwise);
  * O <= 128.
  * ---------------------------------------------------------------------- */

@@ -95,7 +95,15 @@ size_t csp_score_workspace_bytes(const csp_desc* d) {
     const int ck = score_chunk_keys(d->B, d->H_q, d->max_seqlen);
     const size_t n_chunks = (size_t)(d->max_seqlen + ck - 1) / ck;
     (void)c;
-    return (size_t)d->B * d->H_q * n_chunks * d->window_O * 2 * sizeof(float);
+    size_t bytes = (size_t)d->B * d->H_q * n_chunks * d->window_O * 2 * sizeof(float);
+    // per-slice sums of a selection group that is split over several workgroups
+    if (d->sel_group > 1 && d->H_q % d->sel_group == 0) {
+        const int gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, (int)n_chunks);
+        const int gsplit = (d->sel_group + gper - 1) / gper;
+        const size_t total = d->cu_seqlens_host ? (size_t)d->cu_seqlens_host[d->B] : (size_t)d->B * d->max_seqlen;
+        if (gsplit > 1) bytes = ((bytes + 15) & ~(size_t)15) + (size_t)2 * gsplit * (d->H_q / d->sel_group) * total * sizeof(float);
+    }
+    return bytes;
 }
 
 int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t* modality,
@@ -121,6 +129,13 @@ int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t
     p.n_chunks = (d->max_seqlen + p.chunk_keys - 1) / p.chunk_keys;
     p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
     p.total_tokens = c.total_tokens;
+    p.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, p.n_chunks);
+    p.gsplit = (d->sel_group + p.gper - 1) / p.gper;
+    if (p.gsplit > 1) {
+        const size_t base = ((size_t)d->B * d->H_q * p.n_chunks * d->window_O * 2 * sizeof(float) + 15) & ~(size_t)15;
+        p.slice_self = reinterpret_cast<float*>(static_cast<char*>(ws) + base);
+        p.slice_cross = p.slice_self + (size_t)p.gsplit * (d->H_q / d->sel_group) * c.total_tokens;
+    }
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
     p.n_score = (float)d->n_score;
     return launch_score(p, d->dtype, d->D, d->max_seqlen, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;

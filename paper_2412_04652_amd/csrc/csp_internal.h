@@ -37,9 +37,12 @@ struct ScoreParams {
     float* score_self;
     float* score_cross;
     float* part;          // [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units
+    float* slice_self;    // [gsplit][H_sel][total] per-slice sums of a split selection group (gsplit > 1)
+    float* slice_cross;
     const int32_t* cu;
     int32_t B, H_q, G, sel_group, O, R, causal;
     int32_t n_chunks, chunk_keys;
+    int32_t gsplit, gper;  // a selection group is summed in gsplit slices of gper consecutive heads
     int64_t k_stride_tok, k_stride_head;  // elements
     int64_t total_tokens;
     float scale_log2;     // log2(e) / sqrt(D)
@@ -109,6 +112,8 @@ hipError_t launch_decode(const DecodeParams& p, int dtype, int D, hipStream_t s)
 
 // host-side sizing rules shared by the *_workspace_bytes functions and the launchers
 int score_chunk_keys(int B, int H_q, int max_seqlen);
+// heads of a selection group that one workgroup of the column-sum pass sums itself
+int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks);
 int decode_num_splits(int B, int H_kv, int max_kv_len);
 
 }  // namespace csp

@@ -416,7 +416,9 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     using QF = QFrags<E, D, NQB, kQbLds>;
     using SM = Smem<E, D, NQB, kQbLds>;
     extern __shared__ __align__(16) char smem[];
-    const int chunk = blockIdx.x, sg = blockIdx.y, b = blockIdx.z;
+    // blockIdx.y = (selection group, slice of its heads); a group summed by one workgroup
+    // (gsplit == 1) writes the result, otherwise each slice writes its own partial array
+    const int chunk = blockIdx.x, sg = blockIdx.y / p.gsplit, slice = blockIdx.y % p.gsplit, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int seq0 = p.cu[b];
     const int L = p.cu[b + 1] - seq0;
@@ -424,6 +426,10 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     if (c0 >= L) return;
     const int O = p.O, R = p.R;
     const float c = p.scale_log2;
+    const int g_begin = slice * p.gper, g_end = min(p.sel_group, g_begin + p.gper);
+    const size_t slice_off = (size_t)slice * (size_t)(p.H_q / p.sel_group) * p.total_tokens;
+    float* const out_self = p.gsplit > 1 ? p.slice_self + slice_off : p.score_self;
+    float* const out_cross = p.gsplit > 1 ? p.slice_cross + slice_off : p.score_cross;
     const float NEG_INF = -__builtin_inff();
     const int n_chunks_b = (L + p.chunk_keys - 1) / p.chunk_keys;
 
@@ -471,7 +477,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
         return p.modality[seq0 + (j < L ? j : L - 1)];
     };
 
-    for (int g = 0; g < p.sel_group; ++g) {
+    for (int g = g_begin; g < g_end; ++g) {
         const int hq = sg * p.sel_group + g;
         const int hk = hq / p.G;
         // the key stream starts first; the per-head set-up below overlaps with it
@@ -567,17 +573,29 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
                     float s_self = key_text ? ct : cv;
                     float s_cross = key_text ? cv : ct;
                     const size_t o = (size_t)sg * p.total_tokens + seq0 + j;
-                    if (g > 0) {  // same thread wrote these in the previous head iteration
-                        s_self += p.score_self[o];
-                        s_cross += p.score_cross[o];
+                    if (g > g_begin) {  // same thread wrote these in the previous head iteration
+                        s_self += out_self[o];
+                        s_cross += out_cross[o];
                     }
-                    p.score_self[o] = s_self;
-                    p.score_cross[o] = s_cross;
+                    out_self[o] = s_self;
+                    out_cross[o] = s_cross;
                 }
             }
         }
         }
     }
+}
+
+// Sum of the per-slice arrays of a split selection group, slices in ascending order
+// (a fixed order: the result does not depend on scheduling).
+__global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
+    const size_t n = (size_t)(p.H_q / p.sel_group) * p.total_tokens;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float* src = blockIdx.y == 0 ? p.slice_self : p.slice_cross;
+    float acc = __builtin_nontemporal_load(src + i);
+    for (int sl = 1; sl < p.gsplit; ++sl) acc += __builtin_nontemporal_load(src + (size_t)sl * n + i);
+    (blockIdx.y == 0 ? p.score_self : p.score_cross)[i] = acc;
 }
 
 template <typename E, int D, int NQB>
@@ -595,11 +613,15 @@ hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
     }
     const dim3 block(kThreads);
     const dim3 grid_a(p.n_chunks, p.H_q, p.B);
-    const dim3 grid_b(p.n_chunks, p.H_q / p.sel_group, p.B);
+    const dim3 grid_b(p.n_chunks, (p.H_q / p.sel_group) * p.gsplit, p.B);
     hipLaunchKernelGGL(ka, grid_a, block, smem_a, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kb, grid_b, block, smem_b, s, p);
+    e = hipGetLastError();
+    if (e != hipSuccess || p.gsplit == 1) return e;
+    const size_t n = (size_t)(p.H_q / p.sel_group) * p.total_tokens;
+    hipLaunchKernelGGL(score_slice_sum_kernel, dim3((unsigned)((n + 255) / 256), 2), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 
@@ -618,6 +640,15 @@ int score_chunk_keys(int B, int H_q, int max_seqlen) {
     int ck = 4096;
     while (ck > 128 && (int64_t)B * H_q * ((max_seqlen + ck - 1) / ck) < 1024) ck >>= 1;
     return ck;
+}
+
+int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks) {
+    // one workgroup sums a whole group while that still leaves about four workgroups per compute
+    // unit; larger groups are cut into equal slices
+    const int64_t groups = (int64_t)B * (H_q / sel_group) * n_chunks;
+    int gper = sel_group;
+    while (gper > 1 && groups * ((sel_group + gper - 1) / gper) < 1024) gper = (gper + 1) / 2;
+    return gper;
 }
 
 hipError_t launch_score(const ScoreParams& p, int dtype, int D, int /*max_seqlen*/, hipStream_t s) {

@@ -108,6 +108,26 @@ def test_7b_16k_layer_sampled(gpu, oracle, budget):
     assert (tot <= 64 * (1 + 1e-3)).all() and (tot > 32).all()
 
 
+def test_7b_16k_head_averaged_sampled(gpu, oracle):
+    """The benchmark workload with the scores summed over all 32 heads (the paper's head axis read
+    literally): one index set per sequence, shared by every KV head.  The selection group is cut
+    into slices summed by separate workgroups here; the oracle sums the 32 heads of one sequence."""
+    import gpu_util as U
+    rng = np.random.default_rng(1000)
+    layouts = [W.layout_7b_16k(rng) for _ in range(4)]
+    T = 8192
+    print("[full] 7b_16k head-averaged", flush=True)
+    lay, q, k, v, mod, cu, dec = _run(gpu, layouts, H_q=32, H_kv=32, D=128, O=64, budgets=[T] * 4, sel_group=32, seed=0)
+    nd = _check_sample(oracle, U, lay, q, k, v, mod, cu, [(2, 0)], O=64, R=64, T_of=lambda b: T, G=1, sel_group=32,
+                       dec=dec, what="7b_16k head-averaged")
+    print(f"[full] keys differing near the threshold: {nd}", flush=True)
+    assert nd <= 4
+    cnt = lay.kept_cnt.cpu().numpy()
+    assert cnt.shape == (4, 1, 4) and (cnt[:, 0, 0] == T).all()
+    tot = (lay.score_self + lay.score_cross).view(4, 16384).sum(-1).cpu().numpy()
+    assert (tot <= 32 * 64 * (1 + 1e-3)).all() and (tot > 32 * 32).all()
+
+
 def test_64k_stress_sampled(gpu, oracle):
     """B=1, 32 heads, L=65536, window 128, budget 10 %, 1 % of the visual keys scaled x4."""
     import gpu_util as U
@@ -140,3 +160,25 @@ def test_gqa_ragged_full_sampled(gpu, oracle):
     for b in range(8):
         assert (cnt[b, :, 0] == budgets[b]).all()
     np.testing.assert_array_equal(lay.kv_len.cpu().numpy(), np.broadcast_to(np.array(budgets)[:, None] + 1, (8, 4)))
+
+
+def test_gqa_large_groups_in_slices(gpu, oracle):
+    """B=8 sequences of 19k-32k tokens, 64 query heads on 8 KV heads (head_dim 64), one index set per
+    KV head: large enough that a group of 8 heads is summed in slices of several heads each (both
+    the in-place accumulation over a slice's heads and the ordered sum of the slices run)."""
+    import gpu_util as U
+    rng = np.random.default_rng(77)
+    layouts = [W.layout_random(rng, [576] * int(n_img), 32768 - 576 * 48 + int(extra), 64)
+               for n_img, extra in zip(rng.integers(30, 49, size=8), rng.integers(-3000, 1, size=8))]
+    layouts[5] = W.layout_random(rng, [576] * 48, 32768 - 576 * 48, 64)   # one sequence at the maximum
+    lens = [sum(n for _, n in s) for s in layouts]
+    assert max(lens) == 32768
+    budgets = [int(l * 0.3) for l in lens]
+    print(f"[full] gqa large lens={lens}", flush=True)
+    lay, q, k, v, mod, cu, dec = _run(gpu, layouts, H_q=64, H_kv=8, D=64, O=64, budgets=budgets, sel_group=8, seed=21)
+    sample = [(5, 0), (1, 7), (6, 3)]
+    _check_sample(oracle, U, lay, q, k, v, mod, cu, sample, O=64, R=64, T_of=lambda b: budgets[b], G=8, sel_group=8,
+                  dec=dec, what="gqa large")
+    cnt = lay.kept_cnt.cpu().numpy()
+    for b in range(8):
+        assert (cnt[b, :, 0] == budgets[b]).all()
