@@ -49,19 +49,26 @@ def parse():
     ap.add_argument("--no-second-budget", action="store_true")
     ap.add_argument("--sel-group", type=int, default=1,
                     help="query heads whose scores are summed into one index set (1 = per head, H = one set per layer)")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip the extra passes over 8 layers: mixed-modality window, n-softmax scoring, cross-ratio sweep")
     ap.add_argument("--no-head-averaged", action="store_true",
                     help="skip the extra pass with one index set per layer (scores summed over all heads)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
-def build_inputs(cfg, n_layers, device):
+def build_inputs(cfg, n_layers, device, window_text=0):
+    """window_text > 0: the sequences end with an image and `window_text` text tokens, so the
+    observation window holds queries of both modalities."""
     import numpy as np
     import csp_workloads as W
     layers = []
     for l in range(n_layers):
         rng = np.random.default_rng(1000 + l)
-        if cfg["L"] == 4096:
+        if window_text:
+            layouts = [W.layout_mixed_window(rng, [cfg["vis"]] * cfg["images"], cfg["text"], window_text)
+                       for _ in range(cfg["B"])]
+        elif cfg["L"] == 4096:
             layouts = [W.layout_7b_4k() for _ in range(cfg["B"])]
         else:
             layouts = [W.layout_random(rng, [cfg["vis"]] * cfg["images"], cfg["text"], cfg["O"]) for _ in range(cfg["B"])]
@@ -71,12 +78,12 @@ def build_inputs(cfg, n_layers, device):
     return layers
 
 
-def make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group=1):
+def make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group=1, cross_ratio=0.5, n_score=0.0):
     from paper_2412_04652_amd.runner import CspLayer
     T = int(cfg["L"] * budget_frac)
     return [CspLayer(dtype="bf16", H_q=cfg["H"], H_kv=cfg["H"], D=cfg["D"], O=cfg["O"], R=cfg["O"],
                      cu_seqlens=inp["cu"], budgets=[T] * cfg["B"], decode_cap=decode_steps, device=device,
-                     sel_group=sel_group)
+                     sel_group=sel_group, cross_ratio=cross_ratio, n_score=n_score)
             for inp in inputs], T
 
 
@@ -154,10 +161,11 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, stre
     b.record()
 
 
-def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_streams=1, sel_group=1):
+def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_streams=1, sel_group=1,
+            cross_ratio=0.5, n_score=0.0):
     import torch
     streams = [torch.cuda.Stream(device=device) for _ in range(n_streams)] if n_streams > 1 else None
-    layers, T = make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group)
+    layers, T = make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group, cross_ratio, n_score)
     g = torch.Generator(device=device); g.manual_seed(777)
     nd = 4
     dec = dict(n=nd,
@@ -202,6 +210,8 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
             "select": dict(ms=avg(ms["select"]), gbps=by_select / (avg(ms["select"]) * 1e-3) / 1e9, bytes=by_select),
             "compact": dict(ms=avg(ms["compact"]), gbps=by_compact / (avg(ms["compact"]) * 1e-3) / 1e9, bytes=by_compact),
         })
+    # kept keys per (sequence, index set): below T when the two top-K sets overlap (mixed windows)
+    res["kept_mean"] = float(torch.stack([l.kept_cnt[:, :, 0].float().mean() for l in layers]).mean())
     if decode_steps > 0:
         dec_ms = avg(ms["decode"])
         call_ms = avg(ms["decode_split"])
@@ -300,6 +310,23 @@ def main():
     if not args.no_head_averaged and args.workload == "7b_16k" and args.sel_group == 1:
         # the paper-literal head axis: scores summed over all heads, one index set per layer and sequence
         head_avg = measure(cfg, inputs, args.budget, 0, 1, 1, device, args.streams, cfg["H"])
+    variants = None
+    if not args.no_variants and args.workload == "7b_16k" and args.sel_group == 1:
+        # same shapes, 8 layers, pruning phase only
+        keys = ("budget", "T", "prune_ms", "tokens_per_s", "prune_gbps", "kept_mean")
+        variants = {}
+        sub = inputs[:8]
+        r = measure(cfg, sub, args.budget, 0, 2, 1, device, args.streams, n_score=1.0)
+        variants["n_score_1"] = {k: r[k] for k in keys}
+        for ratio in (0.0, 0.25, 0.75, 1.0):
+            r = measure(cfg, sub, args.budget, 0, 2, 1, device, args.streams, cross_ratio=ratio)
+            variants[f"cross_ratio_{ratio:g}"] = {k: r[k] for k in keys}
+        mixed = build_inputs(cfg, 8, device, window_text=16)
+        r = measure(cfg, mixed, args.budget, 0, 2, 1, device, args.streams)
+        variants["mixed_window_48v_16t"] = {k: r[k] for k in keys}
+        variants["mixed_window_48v_16t"]["kernels"] = r["kernels"]
+        del mixed
+        torch.cuda.empty_cache()
     peak_copy = copy_peak(device)
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds)
 
@@ -342,6 +369,8 @@ def main():
         out["second_budget"] = {k: second[k] for k in ("budget", "T", "prune_ms", "tokens_per_s", "prune_gbps",
                                                        "decode_gbps", "decode_ms_per_token") if k in second}
         out["second_budget"]["kernels"] = second["kernels"]
+    if variants is not None:
+        out["variants_8_layers"] = variants
     if head_avg is not None:
         out["head_averaged"] = {k: head_avg[k] for k in ("budget", "T", "sel_group", "prune_ms", "tokens_per_s", "prune_gbps")}
         out["head_averaged"]["kernels"] = head_avg["kernels"]

@@ -91,6 +91,16 @@ def layout_random(rng: np.random.Generator, image_lens: Sequence[int], n_text: i
     return spans
 
 
+def layout_mixed_window(rng: np.random.Generator, image_lens: Sequence[int], n_text: int,
+                        window_text: int) -> List[Span]:
+    """As layout_random, but the sequence ends with the last image followed by only
+    `window_text` text tokens: an observation window longer than that holds queries
+    of both modalities."""
+    assert 0 < window_text <= n_text and len(image_lens) >= 1
+    spans = [s for s in layout_random(rng, image_lens[:-1], n_text - window_text, 0) if s[1] > 0]
+    return spans + [(VISUAL, int(image_lens[-1])), (TEXT, int(window_text))]
+
+
 # ----------------------------------------------------------------------------
 # Cases
 # ----------------------------------------------------------------------------

@@ -93,3 +93,22 @@ def assert_kept_equivalent(gpu_idx: np.ndarray, ref_idx: np.ndarray, a_self: np.
         gm = sum(1 for j in gpu_idx if j < L - R and mod[j] == m)
         assert gm == len(kept_m), f"{what}: modality {m} kept {gm} vs {len(kept_m)}"
     return len(diff)
+
+
+def assert_kept_equivalent_mixed(gpu_idx: np.ndarray, ref_idx: np.ndarray, a_self: np.ndarray, a_cross: np.ndarray,
+                                 K_s: int, K_c: int, L: int, R: int, what: str = "") -> int:
+    """A window with both modalities: every prefix key ranks in both regions and the kept set is
+    the union of the two top-K sets plus the recent keys.  A key kept by one side only must have
+    a score within REL of one of the two thresholds (the oracle's K-th largest self / cross score).
+    Returns the number of differing keys."""
+    P = L - R
+    assert (np.diff(gpu_idx) > 0).all(), f"{what}: indices not ascending/unique"
+    assert gpu_idx[-R:].tolist() == list(range(P, L)), f"{what}: recent keys missing"
+    diff = sorted(set(gpu_idx.tolist()) ^ set(ref_idx.tolist()))
+    tau_s = np.sort(a_self[:P])[P - K_s] if K_s > 0 else np.inf
+    tau_c = np.sort(a_cross[:P])[P - K_c] if K_c > 0 else np.inf
+    for j in diff:
+        near_s = K_s > 0 and abs(a_self[j] - tau_s) <= REL * tau_s + ABS_FLOOR * float(np.max(a_self[:P]))
+        near_c = K_c > 0 and abs(a_cross[j] - tau_c) <= REL * tau_c + ABS_FLOOR * float(np.max(a_cross[:P]))
+        assert near_s or near_c, f"{what}: key {j} differs, self {a_self[j]!r} vs {tau_s!r}, cross {a_cross[j]!r} vs {tau_c!r}"
+    return len(diff)
