@@ -13,6 +13,8 @@
  *   csp_decode_attn  one decode step of n-softmax attention over that cache
  *   csp_append_kv    append the new token's k, v to the pruned cache
  *   csp_decode_step  append + attend fused into one call
+ *   csp_reprune      the same pruning pass applied in place to the grown cache
+ *                    while decoding (with csp_gather_modality, csp_window_push)
  *
  * Conventions
  *  - "device" pointers are HIP device memory owned by the caller; "host"
@@ -217,6 +219,62 @@ int csp_decode_step_phase(const csp_desc* desc, int32_t phase, const void* q, co
 int csp_append_kv(const csp_desc* desc, const void* k_new, const void* v_new, void* k_cache,
                   void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
                   int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Re-pruning while decoding — the loop of Algorithm 1: at a generation step
+ * the cache (pruned keys plus the tokens appended since) is checked against
+ * the budget T and, when longer, pruned again with the same procedure: the
+ * window is the last O queries, key t of the cache is visible to window row i
+ * iff t <= L-O+i (L = current cache length; cache order is temporal order), the
+ * last R rows are kept unranked, the regions follow the modality of the cached
+ * keys.  The paper does not say how often this runs; the caller decides (every
+ * step, or every few steps so that the cache oscillates between T and T+s).
+ *
+ * csp_gather_modality — companion of csp_compact: the modality of every kept
+ * key next to the pruned cache, because each selection group keeps different
+ * keys:  mod_cache[b][s][t] = modality[cu_seqlens[b] + kept_idx[b][s][t]] for
+ * t < kept, 0 for kept <= t < cache_cap (tokens appended while decoding are
+ * text).
+ *   mod_cache device uint8 [B][H_sel][cache_cap]
+ *
+ * csp_window_push — stores the current step's queries (device [B][H_q][D]) in
+ * slot `slot` (0 <= slot < O) of the ring q_ring (device [B][H_q][O][D]) that
+ * holds the last O queries.
+ *
+ * csp_reprune — score -> select -> in-place compaction over the cache.
+ *   q_ring, ring_start   the last O queries; ring_start is the slot of the
+ *             oldest one (a window already in temporal order: ring_start = 0)
+ *   k_cache, v_cache, strides, cache_cap, kv_len   as in csp_decode_step; kv_len
+ *             is read (all KV heads of a selection group must agree) and
+ *             receives the kept count
+ *   mod_cache as above; kept flags are moved with their keys, the freed tail
+ *             is cleared
+ *   score_self, score_cross  device float [B][H_sel][cache_cap], written for
+ *             the ranked keys of every sequence that is pruned
+ *   kept_idx, kept_cap, kept_cnt   as in csp_select (cache positions); kept_cap
+ *             >= every T_b
+ *   ws        device scratch of csp_reprune_workspace_bytes(desc, cache_cap)
+ * A sequence with kv_len <= T_b is left untouched (its scores are not
+ * written, its kept_idx is the identity).  Requires T_b >= max(O, R) for every
+ * b (CSP_EINVAL otherwise), so that a sequence that is pruned holds a full
+ * window.  Descriptor fields read: dtype, B, H_q, H_kv, D, sel_group, window_O,
+ * recent_R, causal, n_score, cross_ratio, budget_T_host, budget_T; cu_seqlens,
+ * max_seqlen and the K/V strides are not used.
+ * The compaction moves rows down inside one buffer: a workgroup owns one
+ * (sequence, KV head) and orders its reads before its writes block by block;
+ * K, V and mod_cache must not be accessed by other work until the call's
+ * kernels have finished.
+ * ---------------------------------------------------------------------- */
+int csp_gather_modality(const csp_desc* desc, const uint8_t* modality, const int32_t* kept_idx,
+                        int32_t kept_cap, const int32_t* kept_cnt, uint8_t* mod_cache,
+                        int32_t cache_cap, void* stream);
+int csp_window_push(const csp_desc* desc, const void* q_new, void* q_ring, int32_t slot, void* stream);
+size_t csp_reprune_workspace_bytes(const csp_desc* desc, int32_t cache_cap);
+int csp_reprune(const csp_desc* desc, const void* q_ring, int32_t ring_start,
+                void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                int64_t cache_stride_tok, int32_t cache_cap, uint8_t* mod_cache, int32_t* kv_len,
+                float* score_self, float* score_cross, int32_t* kept_idx, int32_t kept_cap,
+                int32_t* kept_cnt, void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

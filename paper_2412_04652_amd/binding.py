@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = [
     "csp_compact",
     "csp_decode_workspace_bytes", "csp_decode_attn", "csp_decode_step", "csp_decode_step_phase",
     "csp_append_kv",
+    "csp_gather_modality", "csp_window_push", "csp_reprune_workspace_bytes", "csp_reprune",
 ]
 
 
@@ -67,6 +68,11 @@ def load_library():
         L.csp_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]; L.csp_decode_step.restype = C.c_int
         L.csp_decode_step_phase.argtypes = [dp, i32, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]; L.csp_decode_step_phase.restype = C.c_int
         L.csp_append_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]; L.csp_append_kv.restype = C.c_int
+        L.csp_gather_modality.argtypes = [dp, vp, vp, i32, vp, vp, i32, vp]; L.csp_gather_modality.restype = C.c_int
+        L.csp_window_push.argtypes = [dp, vp, vp, i32, vp]; L.csp_window_push.restype = C.c_int
+        L.csp_reprune_workspace_bytes.argtypes = [dp, i32]; L.csp_reprune_workspace_bytes.restype = sz
+        L.csp_reprune.argtypes = [dp, vp, i32, vp, vp, i64, i64, i64, i32, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
+        L.csp_reprune.restype = C.c_int
         _lib = L
     return _lib
 
@@ -194,3 +200,26 @@ def csp_decode_step_phase(desc: Desc, phase: int, q, k_new, v_new, k_cache, v_ca
                                                 _ptr(v_cache), int(cache_strides[0]), int(cache_strides[1]),
                                                 int(cache_strides[2]), int(cache_cap), _ptr(kv_len), _ptr(out), _ptr(ws),
                                                 _nbytes(ws), _stream(stream)), "csp_decode_step_phase")
+
+
+def csp_gather_modality(desc: Desc, modality, kept_idx, kept_cap: int, kept_cnt, mod_cache, cache_cap: int,
+                        stream=None) -> None:
+    _check(load_library().csp_gather_modality(desc.ref(), _ptr(modality), _ptr(kept_idx), int(kept_cap), _ptr(kept_cnt),
+                                              _ptr(mod_cache), int(cache_cap), _stream(stream)), "csp_gather_modality")
+
+
+def csp_window_push(desc: Desc, q_new, q_ring, slot: int, stream=None) -> None:
+    _check(load_library().csp_window_push(desc.ref(), _ptr(q_new), _ptr(q_ring), int(slot), _stream(stream)),
+           "csp_window_push")
+
+
+def csp_reprune_workspace_bytes(desc: Desc, cache_cap: int) -> int:
+    return int(load_library().csp_reprune_workspace_bytes(desc.ref(), int(cache_cap)))
+
+
+def csp_reprune(desc: Desc, q_ring, ring_start: int, k_cache, v_cache, cache_strides, cache_cap: int, mod_cache, kv_len,
+                score_self, score_cross, kept_idx, kept_cap: int, kept_cnt, ws, stream=None) -> None:
+    _check(load_library().csp_reprune(desc.ref(), _ptr(q_ring), int(ring_start), _ptr(k_cache), _ptr(v_cache),
+                                      int(cache_strides[0]), int(cache_strides[1]), int(cache_strides[2]), int(cache_cap),
+                                      _ptr(mod_cache), _ptr(kv_len), _ptr(score_self), _ptr(score_cross), _ptr(kept_idx),
+                                      int(kept_cap), _ptr(kept_cnt), _ptr(ws), _nbytes(ws), _stream(stream)), "csp_reprune")

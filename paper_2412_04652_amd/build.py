@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libcsp.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "decode.hip"]
+SOURCES = ["api.hip", "score.hip", "select.hip", "compact.hip", "decode.hip", "reprune.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -122,13 +122,13 @@ int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t
     p.q_win = q_win; p.k = k; p.modality = modality;
     p.score_self = score_self; p.score_cross = score_cross;
     p.part = static_cast<float*>(ws);
-    p.cu = d->cu_seqlens;
+    p.view.cu = d->cu_seqlens; p.view.H_kv = d->H_kv; p.view.H_sel = c.H_sel; p.view.total_tokens = c.total_tokens;
+    p.score_elems = (int64_t)c.H_sel * c.total_tokens;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
     p.chunk_keys = score_chunk_keys(d->B, d->H_q, d->max_seqlen);
     p.n_chunks = (d->max_seqlen + p.chunk_keys - 1) / p.chunk_keys;
     p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
-    p.total_tokens = c.total_tokens;
     p.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, p.n_chunks);
     p.gsplit = (d->sel_group + p.gper - 1) / p.gper;
     if (p.gsplit > 1) {
@@ -154,10 +154,10 @@ int csp_select(const csp_desc* d, const float* score_self, const float* score_cr
     SelectParams p;
     std::memset(&p, 0, sizeof(p));
     p.score_self = score_self; p.score_cross = score_cross; p.modality = modality;
-    p.cu = d->cu_seqlens; p.budget_T = d->budget_T;
+    p.view.cu = d->cu_seqlens; p.view.H_kv = d->H_kv; p.view.H_sel = c.H_sel; p.view.total_tokens = c.total_tokens;
+    p.budget_T = d->budget_T;
     p.kept_idx = kept_idx; p.kept_cnt = kept_cnt;
     p.B = d->B; p.H_sel = c.H_sel; p.O = d->window_O; p.R = d->recent_R; p.kept_cap = kept_cap;
-    p.total_tokens = c.total_tokens;
     p.cross_ratio = d->cross_ratio;
     return launch_select(p, d->max_seqlen, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
 }
@@ -264,6 +264,131 @@ int csp_append_kv(const csp_desc* d, const void* k_new, const void* v_new, void*
     p.B = d->B; p.H_kv = d->H_kv; p.cache_cap = cache_cap; p.row_bytes = c.row_bytes;
     p.stride_b = cache_stride_b * c.EB; p.stride_head = cache_stride_head * c.EB; p.stride_tok = cache_stride_tok * c.EB;
     return launch_append(p, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+int csp_gather_modality(const csp_desc* d, const uint8_t* modality, const int32_t* kept_idx, int32_t kept_cap,
+                        const int32_t* kept_cnt, uint8_t* mod_cache, int32_t cache_cap, void* stream) {
+    Checked c;
+    int rc = check_desc(d, true, &c);
+    if (rc != CSP_OK) return rc;
+    if (!modality || !kept_idx || !kept_cnt || !mod_cache || kept_cap <= 0 || cache_cap <= 0) return CSP_EINVAL;
+    ModGatherParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.modality = modality; p.cu = d->cu_seqlens; p.kept_idx = kept_idx; p.kept_cnt = kept_cnt; p.mod_out = mod_cache;
+    p.B = d->B; p.H_sel = c.H_sel; p.kept_cap = kept_cap; p.mod_cap = cache_cap;
+    return launch_mod_gather(p, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+int csp_window_push(const csp_desc* d, const void* q_new, void* q_ring, int32_t slot, void* stream) {
+    Checked c;
+    int rc = check_desc(d, false, &c);
+    if (rc != CSP_OK) return rc;
+    if (!q_new || !q_ring || !aligned16(q_new) || !aligned16(q_ring)) return CSP_EINVAL;
+    if (d->window_O <= 0 || d->window_O > 128 || slot < 0 || slot >= d->window_O) return CSP_EINVAL;
+    WindowParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.src = q_new; p.dst = q_ring; p.rows = d->B * d->H_q; p.O = d->window_O; p.row_bytes = c.row_bytes; p.slot = slot;
+    return launch_window_push(p, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+namespace {
+struct RepruneLayout {
+    int chunk_keys, n_chunks, gper, gsplit;
+    size_t off_part, off_slices, total;
+};
+RepruneLayout reprune_layout(const csp_desc* d, int H_sel, int row_bytes, int cache_cap) {
+    RepruneLayout l;
+    l.chunk_keys = score_chunk_keys(d->B, d->H_q, cache_cap);
+    l.n_chunks = (cache_cap + l.chunk_keys - 1) / l.chunk_keys;
+    l.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, l.n_chunks);
+    l.gsplit = (d->sel_group + l.gper - 1) / l.gper;
+    auto up = [](size_t x) { return (x + 15) & ~(size_t)15; };
+    l.off_part = up((size_t)d->B * d->H_q * d->window_O * row_bytes);                  // the window in temporal order
+    l.off_slices = l.off_part + up((size_t)d->B * d->H_q * l.n_chunks * d->window_O * 2 * sizeof(float));
+    l.total = l.off_slices + (l.gsplit > 1 ? (size_t)2 * l.gsplit * d->B * H_sel * cache_cap * sizeof(float) : 0);
+    return l;
+}
+}  // namespace
+
+size_t csp_reprune_workspace_bytes(const csp_desc* d, int32_t cache_cap) {
+    if (!d || d->B <= 0 || d->H_q <= 0 || d->H_kv <= 0 || d->window_O <= 0 || cache_cap <= 0) return 0;
+    if (d->sel_group <= 0 || d->H_q % d->sel_group != 0) return 0;
+    const int EB = d->dtype == CSP_BF16 ? 2 : 4;
+    return reprune_layout(d, d->H_q / d->sel_group, d->D * EB, cache_cap).total;
+}
+
+int csp_reprune(const csp_desc* d, const void* q_ring, int32_t ring_start, void* k_cache, void* v_cache,
+                int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok, int32_t cache_cap,
+                uint8_t* mod_cache, int32_t* kv_len, float* score_self, float* score_cross, int32_t* kept_idx,
+                int32_t kept_cap, int32_t* kept_cnt, void* ws, size_t ws_bytes, void* stream) {
+    Checked c;
+    int rc = check_desc(d, false, &c);
+    if (rc != CSP_OK) return rc;
+    if (!q_ring || !k_cache || !v_cache || !mod_cache || !kv_len || !score_self || !score_cross || !kept_idx || !kept_cnt)
+        return CSP_EINVAL;
+    if (!aligned16(q_ring) || !aligned16(k_cache) || !aligned16(v_cache)) return CSP_EINVAL;
+    if (d->window_O <= 0 || d->recent_R < 0) return CSP_EINVAL;
+    if (d->window_O > 128) return CSP_EUNSUPPORTED;
+    if (ring_start < 0 || ring_start >= d->window_O || cache_cap <= 0 || kept_cap <= 0) return CSP_EINVAL;
+    if ((rc = check_kv_strides(cache_stride_tok, cache_stride_head, d->D, c.EB)) != CSP_OK) return rc;
+    if (cache_stride_b < 0 || (cache_stride_b * c.EB) % 16 != 0) return CSP_EINVAL;
+    if (!d->budget_T_host || !d->budget_T) return CSP_EINVAL;
+    for (int b = 0; b < d->B; ++b) {
+        const int T = d->budget_T_host[b];
+        if (T < d->window_O || T < d->recent_R || T > kept_cap) return CSP_EINVAL;
+    }
+    const RepruneLayout l = reprune_layout(d, c.H_sel, c.row_bytes, cache_cap);
+    if (!ws || ws_bytes < l.total || !aligned16(ws)) return CSP_EWORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char* wsb = static_cast<char*>(ws);
+
+    WindowParams w;
+    std::memset(&w, 0, sizeof(w));
+    w.src = q_ring; w.dst = wsb; w.rows = d->B * d->H_q; w.O = d->window_O; w.row_bytes = c.row_bytes; w.slot = ring_start;
+    if (launch_window_unroll(w, st) != hipSuccess) return CSP_EHIP;
+
+    SeqView view;
+    std::memset(&view, 0, sizeof(view));
+    view.kv_len = kv_len; view.budget_T = d->budget_T;
+    view.H_kv = d->H_kv; view.H_sel = c.H_sel; view.cap = cache_cap;
+    view.k_stride_batch = cache_stride_b;
+
+    ScoreParams p;
+    std::memset(&p, 0, sizeof(p));
+    p.q_win = wsb; p.k = k_cache; p.modality = mod_cache;
+    p.score_self = score_self; p.score_cross = score_cross;
+    p.part = reinterpret_cast<float*>(wsb + l.off_part);
+    p.view = view;
+    p.score_elems = (int64_t)d->B * c.H_sel * cache_cap;
+    p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
+    p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
+    p.chunk_keys = l.chunk_keys; p.n_chunks = l.n_chunks; p.gper = l.gper; p.gsplit = l.gsplit;
+    if (l.gsplit > 1) {
+        p.slice_self = reinterpret_cast<float*>(wsb + l.off_slices);
+        p.slice_cross = p.slice_self + (size_t)l.gsplit * p.score_elems;
+    }
+    p.k_stride_tok = cache_stride_tok; p.k_stride_head = cache_stride_head;
+    p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
+    p.n_score = (float)d->n_score;
+    if (launch_score(p, d->dtype, d->D, cache_cap, st) != hipSuccess) return CSP_EHIP;
+
+    SelectParams sp;
+    std::memset(&sp, 0, sizeof(sp));
+    sp.score_self = score_self; sp.score_cross = score_cross; sp.modality = mod_cache;
+    sp.view = view; sp.budget_T = d->budget_T;
+    sp.kept_idx = kept_idx; sp.kept_cnt = kept_cnt;
+    sp.B = d->B; sp.H_sel = c.H_sel; sp.O = d->window_O; sp.R = d->recent_R; sp.kept_cap = kept_cap;
+    sp.cross_ratio = d->cross_ratio;
+    if (launch_select(sp, cache_cap, st) != hipSuccess) return CSP_EHIP;
+
+    RepruneParams rp;
+    std::memset(&rp, 0, sizeof(rp));
+    rp.k_cache = k_cache; rp.v_cache = v_cache; rp.mod_cache = mod_cache;
+    rp.kept_idx = kept_idx; rp.kept_cnt = kept_cnt; rp.budget_T = d->budget_T; rp.kv_len = kv_len;
+    rp.B = d->B; rp.H_kv = d->H_kv; rp.H_sel = c.H_sel; rp.kv_per_sel = c.kv_per_sel;
+    rp.kept_cap = kept_cap; rp.cache_cap = cache_cap;
+    rp.stride_b = cache_stride_b * c.EB; rp.stride_head = cache_stride_head * c.EB; rp.stride_tok = cache_stride_tok * c.EB;
+    return launch_reprune_move(rp, c.row_bytes, st) == hipSuccess ? CSP_OK : CSP_EHIP;
 }
 
 }  // extern "C"

@@ -29,6 +29,43 @@ __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 __device__ __forceinline__ float fast_log2(float x) { return __builtin_amdgcn_logf(x); }
 
+// ---- where a sequence's keys, modality flags and scores live ------------------
+// Packed form (pruning after prefill): the rows of all sequences back to back on one token
+// axis, lengths from cu_seqlens, modality [total], scores [H_sel][total].
+// Cache form (re-pruning the grown cache): keys in the pruned cache [B][H_kv][cap][D], live
+// lengths on the device, modality and scores per (sequence, selection group) [B][H_sel][cap].
+struct SeqView {
+    const int32_t* cu;        // packed: [B+1]
+    const int32_t* kv_len;    // cache: [B][H_kv]; nullptr selects the packed form
+    const int32_t* budget_T;  // cache: a sequence with kv_len <= budget is left alone
+    int32_t H_kv, H_sel, cap;
+    int64_t total_tokens;     // packed
+    int64_t k_stride_batch;   // cache: elements between sequences
+};
+
+// live keys of sequence b as seen by KV head hk (all heads of a selection group agree)
+__device__ __forceinline__ int view_len(const SeqView& v, int b, int hk) {
+    if (!v.kv_len) return v.cu[b + 1] - v.cu[b];
+    const int n = v.kv_len[b * v.H_kv + hk];
+    return n < 0 ? 0 : (n > v.cap ? v.cap : n);  // a device-side count is never trusted beyond the capacity
+}
+// cache form only: the sequence already fits its budget, nothing is scored or moved
+__device__ __forceinline__ bool view_fits(const SeqView& v, int b, int L) {
+    return v.kv_len != nullptr && L <= v.budget_T[b];
+}
+// first key of sequence b in the modality array of selection group sg
+__device__ __forceinline__ int64_t view_mod0(const SeqView& v, int b, int sg) {
+    return v.kv_len ? ((int64_t)b * v.H_sel + sg) * v.cap : (int64_t)v.cu[b];
+}
+// ... in the score arrays of selection group sg
+__device__ __forceinline__ int64_t view_score0(const SeqView& v, int b, int sg) {
+    return v.kv_len ? ((int64_t)b * v.H_sel + sg) * v.cap : (int64_t)sg * v.total_tokens + v.cu[b];
+}
+// ... in the key tensor, in elements, without the head term
+__device__ __forceinline__ int64_t view_key0(const SeqView& v, int b, int64_t k_stride_tok) {
+    return v.kv_len ? (int64_t)b * v.k_stride_batch : (int64_t)v.cu[b] * k_stride_tok;
+}
+
 // ---- launch parameter blocks ------------------------------------------------
 struct ScoreParams {
     const void* q_win;
@@ -37,14 +74,14 @@ struct ScoreParams {
     float* score_self;
     float* score_cross;
     float* part;          // [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units
-    float* slice_self;    // [gsplit][H_sel][total] per-slice sums of a split selection group (gsplit > 1)
+    float* slice_self;    // [gsplit][score_elems] per-slice sums of a split selection group (gsplit > 1)
     float* slice_cross;
-    const int32_t* cu;
+    SeqView view;
+    int64_t score_elems;  // floats in score_self (= in score_cross)
     int32_t B, H_q, G, sel_group, O, R, causal;
     int32_t n_chunks, chunk_keys;
     int32_t gsplit, gper;  // a selection group is summed in gsplit slices of gper consecutive heads
     int64_t k_stride_tok, k_stride_head;  // elements
-    int64_t total_tokens;
     float scale_log2;     // log2(e) / sqrt(D)
     float n_score;
 };
@@ -53,12 +90,11 @@ struct SelectParams {
     const float* score_self;
     const float* score_cross;
     const uint8_t* modality;
-    const int32_t* cu;
+    SeqView view;
     const int32_t* budget_T;
     int32_t* kept_idx;
     int32_t* kept_cnt;
     int32_t B, H_sel, O, R, kept_cap;
-    int64_t total_tokens;
     double cross_ratio;
 };
 
@@ -103,12 +139,46 @@ struct DecodeParams {
     float n_decode;
 };
 
+// in-place compaction of the grown cache, modality bookkeeping, window ring
+struct RepruneParams {
+    void* k_cache;
+    void* v_cache;
+    uint8_t* mod_cache;        // [B][H_sel][cache_cap]
+    const int32_t* kept_idx;   // [B][H_sel][kept_cap]
+    const int32_t* kept_cnt;   // [B][H_sel][4]
+    const int32_t* budget_T;
+    int32_t* kv_len;           // [B][H_kv]
+    int32_t B, H_kv, H_sel, kv_per_sel, kept_cap, cache_cap;
+    int64_t stride_b, stride_head, stride_tok;  // bytes
+};
+
+struct ModGatherParams {
+    const uint8_t* modality;   // packed [total]
+    const int32_t* cu;
+    const int32_t* kept_idx;
+    const int32_t* kept_cnt;
+    uint8_t* mod_out;          // [B][H_sel][mod_cap]
+    int32_t B, H_sel, kept_cap, mod_cap;
+};
+
+struct WindowParams {
+    const void* src;
+    void* dst;
+    int32_t rows;              // B * H_q
+    int32_t O, row_bytes;
+    int32_t slot;              // push: ring slot written; unroll: ring slot of the oldest query
+};
+
 // ---- launchers (one per kernel family; each returns a hipError_t) -----------
 hipError_t launch_score(const ScoreParams& p, int dtype, int D, int max_seqlen, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s);
 hipError_t launch_compact(const CompactParams& p, int row_bytes, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_decode(const DecodeParams& p, int dtype, int D, hipStream_t s);
+hipError_t launch_mod_gather(const ModGatherParams& p, hipStream_t s);
+hipError_t launch_reprune_move(const RepruneParams& p, int row_bytes, hipStream_t s);
+hipError_t launch_window_push(const WindowParams& p, hipStream_t s);
+hipError_t launch_window_unroll(const WindowParams& p, hipStream_t s);
 
 // host-side sizing rules shared by the *_workspace_bytes functions and the launchers
 int score_chunk_keys(int B, int H_q, int max_seqlen);

@@ -261,10 +261,10 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     extern __shared__ __align__(16) char smem[];
     const int chunk = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int seq0 = p.cu[b];
-    const int L = p.cu[b + 1] - seq0;
+    const int hk = hq / p.G;
+    const int L = view_len(p.view, b, hk);
     const int c0 = chunk * p.chunk_keys;
-    if (c0 >= L) return;
+    if (c0 >= L || view_fits(p.view, b, L)) return;
     const int O = p.O;
     const float c = p.scale_log2;
     const float NEG_INF = -__builtin_inff();
@@ -273,8 +273,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     float2* red = reinterpret_cast<float2*>(smem + SM::off_red);
     float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
 
-    const int hk = hq / p.G;
-    const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
+    const char* kbase = reinterpret_cast<const char*>(p.k) + (view_key0(p.view, b, p.k_stride_tok) + (int64_t)hk * p.k_stride_head) * G::EB;
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
@@ -420,14 +419,16 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     // (gsplit == 1) writes the result, otherwise each slice writes its own partial array
     const int chunk = blockIdx.x, sg = blockIdx.y / p.gsplit, slice = blockIdx.y % p.gsplit, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int seq0 = p.cu[b];
-    const int L = p.cu[b + 1] - seq0;
+    const int L = view_len(p.view, b, (sg * p.sel_group) / p.G);
     const int c0 = chunk * p.chunk_keys;
-    if (c0 >= L) return;
+    if (c0 >= L || view_fits(p.view, b, L)) return;
     const int O = p.O, R = p.R;
     const float c = p.scale_log2;
+    const uint8_t* const mod = p.modality + view_mod0(p.view, b, sg);
+    const int64_t key0 = view_key0(p.view, b, p.k_stride_tok);
+    const size_t score0 = (size_t)view_score0(p.view, b, sg);
     const int g_begin = slice * p.gper, g_end = min(p.sel_group, g_begin + p.gper);
-    const size_t slice_off = (size_t)slice * (size_t)(p.H_q / p.sel_group) * p.total_tokens;
+    const size_t slice_off = (size_t)slice * (size_t)p.score_elems;
     float* const out_self = p.gsplit > 1 ? p.slice_self + slice_off : p.score_self;
     float* const out_cross = p.gsplit > 1 ? p.slice_cross + slice_off : p.score_cross;
     const float NEG_INF = -__builtin_inff();
@@ -439,7 +440,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
 
     // modality of the window rows; a window with one modality takes the fast path
-    if (tid < NQB * 32) wq[tid] = tid < O ? (p.modality[seq0 + L - O + tid] ? 1 : 0) : 2;
+    if (tid < NQB * 32) wq[tid] = tid < O ? (mod[L - O + tid] ? 1 : 0) : 2;
     __syncthreads();
     bool any_text = false, any_vis = false;
     for (int i = 0; i < O; ++i) {
@@ -474,14 +475,14 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     };
     auto load_mod = [&](int j0) -> uint8_t {  // modality of key j0 + lane%32, fetched with its tile
         const int j = j0 + (lane & 31);
-        return p.modality[seq0 + (j < L ? j : L - 1)];
+        return mod[j < L ? j : L - 1];
     };
 
     for (int g = g_begin; g < g_end; ++g) {
         const int hq = sg * p.sel_group + g;
         const int hk = hq / p.G;
         // the key stream starts first; the per-head set-up below overlaps with it
-        const char* kbase = reinterpret_cast<const char*>(p.k) + ((int64_t)seq0 * p.k_stride_tok + (int64_t)hk * p.k_stride_head) * G::EB;
+        const char* kbase = reinterpret_cast<const char*>(p.k) + (key0 + (int64_t)hk * p.k_stride_head) * G::EB;
         u32x4 st[PF][G::NLD];
         uint8_t kmod[PF];
         if (ntiles > 0) {
@@ -572,7 +573,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
                 if (half == 0 && j < L) {
                     float s_self = key_text ? ct : cv;
                     float s_cross = key_text ? cv : ct;
-                    const size_t o = (size_t)sg * p.total_tokens + seq0 + j;
+                    const size_t o = score0 + j;
                     if (g > g_begin) {  // same thread wrote these in the previous head iteration
                         s_self += out_self[o];
                         s_cross += out_cross[o];
@@ -589,7 +590,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
 // Sum of the per-slice arrays of a split selection group, slices in ascending order
 // (a fixed order: the result does not depend on scheduling).
 __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
-    const size_t n = (size_t)(p.H_q / p.sel_group) * p.total_tokens;
+    const size_t n = (size_t)p.score_elems;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
     const float* src = blockIdx.y == 0 ? p.slice_self : p.slice_cross;
@@ -620,7 +621,7 @@ hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
     hipLaunchKernelGGL(kb, grid_b, block, smem_b, s, p);
     e = hipGetLastError();
     if (e != hipSuccess || p.gsplit == 1) return e;
-    const size_t n = (size_t)(p.H_q / p.sel_group) * p.total_tokens;
+    const size_t n = (size_t)p.score_elems;
     hipLaunchKernelGGL(score_slice_sum_kernel, dim3((unsigned)((n + 255) / 256), 2), dim3(256), 0, s, p);
     return hipGetLastError();
 }

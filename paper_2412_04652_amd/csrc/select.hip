@@ -283,9 +283,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     __shared__ SelShared sh;
     const int sg = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x;
-    const int seq0 = p.cu[b];
     SelCtx c;
-    c.L = p.cu[b + 1] - seq0;
+    c.L = view_len(p.view, b, sg * (p.view.H_kv / p.H_sel));
     c.T = p.budget_T[b];
     c.R = p.R;
     c.kept_cap = p.kept_cap;
@@ -299,9 +298,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
         return;
     }
     c.P = c.L - c.R;  // rankable prefix
-    c.mod = p.modality + seq0;
-    c.sc_self = p.score_self + (size_t)sg * p.total_tokens + seq0;
-    c.sc_cross = p.score_cross + (size_t)sg * p.total_tokens + seq0;
+    c.mod = p.modality + view_mod0(p.view, b, sg);
+    c.sc_self = p.score_self + view_score0(p.view, b, sg);
+    c.sc_cross = p.score_cross + view_score0(p.view, b, sg);
 
     if (tid < 2) sh.has[tid] = 0;
     __syncthreads();

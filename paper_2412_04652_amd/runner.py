@@ -24,7 +24,8 @@ class CspLayer:
     def __init__(self, *, dtype: str, H_q: int, H_kv: int, D: int, O: int, R: int,
                  cu_seqlens: Sequence[int], budgets: Sequence[int], sel_group: int = 1,
                  cross_ratio: float = 0.5, n_score: float = 0.0, n_decode: float = 1.0,
-                 decode_cap: int = 0, device="cuda:0", k_strides=None, v_strides=None, causal: bool = True):
+                 decode_cap: int = 0, device="cuda:0", k_strides=None, v_strides=None, causal: bool = True,
+                 reprune: bool = False):
         self.device = torch.device(device)
         self.dtype, self.H_q, self.H_kv, self.D, self.O, self.R = dtype, H_q, H_kv, D, O, R
         self.B = len(budgets)
@@ -59,6 +60,20 @@ class CspLayer:
         self.ws_decode = torch.empty(max(B_.csp_decode_workspace_bytes(self.desc, self.cache_cap), 16),
                                      dtype=torch.uint8, device=dev)
         self.out = torch.empty((self.B, H_q, D), dtype=torch.float32, device=dev)
+        # re-pruning while decoding: modality of the cached keys, the ring of the last O queries,
+        # scores and kept positions in cache coordinates
+        self.reprune_enabled = reprune
+        if reprune:
+            self.mod_cache = torch.zeros((self.B, self.H_sel, self.cache_cap), dtype=torch.uint8, device=dev)
+            self.q_ring = torch.zeros((self.B, H_q, O, D), dtype=_tdtype(dtype), device=dev)
+            self.pushes = 0
+            self.rp_self = torch.empty((self.B, self.H_sel, self.cache_cap), dtype=torch.float32, device=dev)
+            self.rp_cross = torch.empty((self.B, self.H_sel, self.cache_cap), dtype=torch.float32, device=dev)
+            self.rp_cap = max(self.budgets)
+            self.rp_idx = torch.empty((self.B, self.H_sel, self.rp_cap), dtype=torch.int32, device=dev)
+            self.rp_cnt = torch.empty((self.B, self.H_sel, 4), dtype=torch.int32, device=dev)
+            self.ws_reprune = torch.empty(max(B_.csp_reprune_workspace_bytes(self.desc, self.cache_cap), 16),
+                                          dtype=torch.uint8, device=dev)
 
     # -- the four calls of the path, in order ---------------------------------
     def score(self, q_win, k, modality, stream=None):
@@ -77,6 +92,27 @@ class CspLayer:
         self.score(q_win, k, modality, stream)
         self.select(modality, stream)
         self.compact(k, v, stream)
+        if self.reprune_enabled:
+            B_.csp_gather_modality(self.desc, modality, self.kept_idx, self.kept_cap, self.kept_cnt, self.mod_cache,
+                                   self.cache_cap, stream)
+            # the prefill window, in temporal order: slot 0 is the oldest
+            if stream is None or isinstance(stream, int):
+                self.q_ring.copy_(q_win)
+            else:
+                with torch.cuda.stream(stream):
+                    self.q_ring.copy_(q_win)
+            self.pushes = 0
+
+    def push_query(self, q, stream=None):
+        """records the current step's queries in the ring of the last O"""
+        B_.csp_window_push(self.desc, q, self.q_ring, self.pushes % self.O, stream)
+        self.pushes += 1
+
+    def reprune(self, stream=None):
+        """prunes the grown cache in place (sequences within their budget are left alone)"""
+        B_.csp_reprune(self.desc, self.q_ring, self.pushes % self.O, self.k_cache, self.v_cache, self.cache_strides,
+                       self.cache_cap, self.mod_cache, self.kv_len, self.rp_self, self.rp_cross, self.rp_idx,
+                       self.rp_cap, self.rp_cnt, self.ws_reprune, stream)
 
     def append(self, k_new, v_new, stream=None):
         B_.csp_append_kv(self.desc, k_new, v_new, self.k_cache, self.v_cache, self.cache_strides,

@@ -1,0 +1,212 @@
+"""GPU parity of re-pruning the grown cache while decoding (the loop of Algorithm 1): after the
+first pruning pass and a number of decode steps, csp_reprune scores the cache with the last O
+queries, selects and compacts in place.  The oracle repeats the step on a host copy of the
+cache the GPU held before the call: same scoring, selection and gather functions as for the
+first pass, applied to the cache rows and their gathered modality flags."""
+import numpy as np
+import pytest
+
+import csp_workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2412_04652_amd as P
+    P.load_library()
+    return torch.device("cuda:0")
+
+
+def _util():
+    import gpu_util
+    return gpu_util
+
+
+def _snapshot(U, lay, dtype):
+    return dict(k=U.from_dev_bits(lay.k_cache, dtype), v=U.from_dev_bits(lay.v_cache, dtype),
+                mod=lay.mod_cache.cpu().numpy().copy(), kv_len=lay.kv_len.cpu().numpy().copy())
+
+
+def _f64(oracle, a, dtype):
+    return oracle.bf16_bits_to_f64(a) if dtype == "bf16" else np.asarray(a, np.float64)
+
+
+def _check_reprune(U, oracle, lay, before, window, *, dtype, H_q, H_kv, sel_group, O, R, budgets, n_score, cross_ratio,
+                   sample, what):
+    """window: [B][H_q][O][D] storage values of the last O queries in temporal order (built on the
+    host from the prefill window and the decode queries, not read back from the ring)."""
+    G = H_q // H_kv
+    kv_per_sel = sel_group // G
+    after = _snapshot(U, lay, dtype)
+    idx_all, cnt_all = lay.rp_idx.cpu().numpy(), lay.rp_cnt.cpu().numpy()
+    g_self, g_cross = lay.rp_self.cpu().numpy(), lay.rp_cross.cpu().numpy()
+    n_diff = 0
+    for b, s in sample:
+        hk0 = s * kv_per_sel
+        L, T = int(before["kv_len"][b, hk0]), budgets[b]
+        assert (before["kv_len"][b, hk0:hk0 + kv_per_sel] == L).all()
+        if L <= T:  # within budget: untouched
+            for hk in range(hk0, hk0 + kv_per_sel):
+                assert after["kv_len"][b, hk] == L
+                np.testing.assert_array_equal(after["k"][b, hk, :L], before["k"][b, hk, :L])
+                np.testing.assert_array_equal(after["v"][b, hk, :L], before["v"][b, hk, :L])
+            np.testing.assert_array_equal(after["mod"][b, s], before["mod"][b, s])
+            assert cnt_all[b, s, 0] == L and (idx_all[b, s, :L] == np.arange(L)).all()
+            continue
+        m = before["mod"][b, s, :L]
+        a_s, a_c = np.zeros(L), np.zeros(L)
+        for hq in range(s * sel_group, (s + 1) * sel_group):
+            oracle.head_scores(_f64(oracle, window[b, hq], dtype), _f64(oracle, before["k"][b, hq // G, :L], dtype),
+                               m, R, n_score, True, a_s, a_c)
+        P = L - R
+        U.assert_scores_close(g_self[b, s, :P], a_s[:P], f"{what} b{b} s{s} self")
+        U.assert_scores_close(g_cross[b, s, :P], a_c[:P], f"{what} b{b} s{s} cross")
+        ref_idx, rc = oracle.select(a_s, a_c, m, O, R, T, cross_ratio)
+        n = int(cnt_all[b, s, 0])
+        assert cnt_all[b, s, 1:3].tolist() == [rc["K_s"], rc["K_c"]]
+        gi = idx_all[b, s, :n]
+        wmod = m[L - O:]
+        if wmod.min() == wmod.max():
+            assert n == rc["kept"] == T
+            n_diff += U.assert_kept_equivalent(gi, ref_idx, a_s, a_c, m, L, R, f"{what} b{b} s{s}")
+        else:
+            assert abs(n - rc["kept"]) <= 3 and n <= T
+            n_diff += U.assert_kept_equivalent_mixed(gi, ref_idx, a_s, a_c, rc["K_s"], rc["K_c"], L, R, f"{what} b{b} s{s}")
+        assert (idx_all[b, s, n:] == -1).all()
+        # the compaction is a bit copy of the rows the GPU selected, flags moved with them, tail cleared
+        for hk in range(hk0, hk0 + kv_per_sel):
+            assert after["kv_len"][b, hk] == n
+            np.testing.assert_array_equal(after["k"][b, hk, :n], oracle.gather(before["k"][b, hk, :L], gi))
+            np.testing.assert_array_equal(after["v"][b, hk, :n], oracle.gather(before["v"][b, hk, :L], gi))
+        np.testing.assert_array_equal(after["mod"][b, s, :n], m[gi])
+        assert (after["mod"][b, s, n:] == 0).all()
+    return n_diff
+
+
+def _decode_and_check(U, oracle, dc, case, t, sample_heads):
+    """one decode step (append + attend + ring push) and the oracle's attention over the cache the GPU holds"""
+    lay = dc.layer
+    dq = U.to_dev(case.dec_q[t], case.dtype)
+    dk = U.to_dev(case.dec_k[t], case.dtype)
+    dv = U.to_dev(case.dec_v[t], case.dtype)
+    lay.decode_step(dq, dk, dv)
+    lay.push_query(dq)
+    if not sample_heads:
+        return
+    torch.cuda.synchronize()
+    out = lay.out.cpu().numpy()
+    kv_len = lay.kv_len.cpu().numpy()
+    G = case.H_q // case.H_kv
+    kc, vc = U.from_dev_bits(lay.k_cache, case.dtype), U.from_dev_bits(lay.v_cache, case.dtype)
+    for b, hq in sample_heads:
+        n = int(kv_len[b, hq // G])
+        ref = oracle.decode(_f64(oracle, case.dec_q[t, b, hq], case.dtype), _f64(oracle, kc[b, hq // G, :n], case.dtype),
+                            _f64(oracle, vc[b, hq // G, :n], case.dtype), case.n_decode)
+        U.assert_decode_close(out[b, hq], ref, f"decode t{t} b{b} h{hq}")
+
+
+def _window(case, t_done):
+    """last O queries after t_done decode steps, temporal order: [B][H_q][O][D]"""
+    hist = np.concatenate([case.q_win, np.moveaxis(case.dec_q[:t_done], 0, 2)], axis=2)
+    return hist[:, :, -case.O:]
+
+
+CASES = {
+    # name: (make_case overrides, decode steps before each re-pruning)
+    "per_head": (dict(H_q=2, H_kv=2, sel_group=1, layouts=[[(0, 100), (1, 300), (0, 40)], [(0, 30), (1, 40), (0, 20)]],
+                      budgets=[200, 120]), [5, 8, 3]),
+    "gqa_group": (dict(H_q=8, H_kv=2, sel_group=4, layouts=[[(0, 200), (1, 700), (0, 124)]], budgets=[512]), [16, 1]),
+    "one_set_per_layer": (dict(H_q=4, H_kv=4, sel_group=4, layouts=[[(1, 300), (0, 200)], [(0, 64), (1, 500), (0, 64)]],
+                               budgets=[256, 300]), [10, 10]),
+    "f32_d64": (dict(dtype="f32", D=64, H_q=2, H_kv=1, sel_group=2, layouts=[[(0, 80), (1, 160), (0, 33)]],
+                     budgets=[100]), [7, 2]),
+    "window_still_holds_prefill_visual_queries": (dict(H_q=2, H_kv=2, sel_group=1, O=16, R=16,
+                                                       layouts=[[(0, 100), (1, 290), (0, 10)]], budgets=[200]), [4, 20]),
+    "n_softmax_scoring_ratio": (dict(H_q=2, H_kv=2, sel_group=1, n_score=1.0, cross_ratio=0.3,
+                                     layouts=[[(0, 100), (1, 300), (0, 40)]], budgets=[150]), [9]),
+    "several_tiles_and_chunks": (dict(H_q=4, H_kv=4, sel_group=1, O=64, R=64,
+                                      layouts=[[(0, 500), (1, 2304), (0, 700), (1, 1152), (0, 344)]], budgets=[2500]),
+                                 [70, 64]),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_reprune_cycles(gpu, oracle, name):
+    U = _util()
+    over, cycles = CASES[name]
+    base = dict(dtype="bf16", H_q=2, H_kv=2, D=128, O=8, R=8, sel_group=1, seed=5)
+    base.update(over)
+    steps = sum(cycles)
+    case = W.make_case(name, decode_steps=steps, **base)
+    print(f"[reprune] {name} cycles={cycles}", flush=True)
+    dc = U.DeviceCase(case, decode_cap=max(cycles) + 1, reprune=True)
+    lay = dc.layer
+    lay.prune(dc.q_win, dc.k, dc.v, dc.modality)
+    torch.cuda.synchronize()
+    # modality flags gathered next to the cache: those of the kept keys, zero beyond
+    cnt, idx = lay.kept_cnt.cpu().numpy(), lay.kept_idx.cpu().numpy()
+    modc = lay.mod_cache.cpu().numpy()
+    for b in range(case.B):
+        lo = int(case.cu_seqlens[b])
+        for s in range(lay.H_sel):
+            n = int(cnt[b, s, 0])
+            np.testing.assert_array_equal(modc[b, s, :n], case.modality[lo + idx[b, s, :n]])
+            assert (modc[b, s, n:] == 0).all()
+    sample = [(b, s) for b in range(case.B) for s in range(lay.H_sel)]
+    t = 0
+    budgets = case.budget_T.tolist()
+    for ci, n_steps in enumerate(cycles):
+        for _ in range(n_steps):
+            _decode_and_check(U, oracle, dc, case, t, [(0, 0), (case.B - 1, case.H_q - 1)] if t % 4 == 0 else [])
+            t += 1
+        torch.cuda.synchronize()
+        before = _snapshot(U, lay, case.dtype)
+        lay.reprune()
+        torch.cuda.synchronize()
+        _check_reprune(U, oracle, lay, before, _window(case, t), dtype=case.dtype, H_q=case.H_q, H_kv=case.H_kv,
+                       sel_group=case.sel_group, O=case.O, R=case.R, budgets=budgets, n_score=case.n_score,
+                       cross_ratio=case.cross_ratio, sample=sample, what=f"{name} cycle {ci}")
+
+
+def test_reprune_within_budget_is_a_no_op(gpu, oracle):
+    """No sequence is over its budget: nothing moves, lengths and flags stay."""
+    U = _util()
+    case = W.make_case("noop", dtype="bf16", H_q=2, H_kv=2, D=128, O=8, R=8, layouts=[[(0, 40), (1, 60), (0, 40)]],
+                       budgets=[150], seed=2, decode_steps=3)
+    dc = U.DeviceCase(case, decode_cap=4, reprune=True)
+    lay = dc.layer
+    lay.prune(dc.q_win, dc.k, dc.v, dc.modality)
+    for t in range(3):
+        _decode_and_check(U, oracle, dc, case, t, [])
+    torch.cuda.synchronize()
+    assert lay.kv_len.cpu().numpy().tolist() == [[143, 143]]
+    before = _snapshot(U, lay, "bf16")
+    lay.reprune()
+    torch.cuda.synchronize()
+    _check_reprune(U, oracle, lay, before, _window(case, 3), dtype="bf16", H_q=2, H_kv=2, sel_group=1, O=8, R=8,
+                   budgets=[150], n_score=0.0, cross_ratio=0.5, sample=[(0, 0), (0, 1)], what="noop")
+    assert lay.kv_len.cpu().numpy().tolist() == [[143, 143]]
+
+
+def test_reprune_deterministic(gpu, oracle):
+    U = _util()
+    case = W.make_case("det", dtype="bf16", H_q=4, H_kv=2, D=128, O=16, R=16, sel_group=2,
+                       layouts=[[(0, 300), (1, 900), (0, 200)]], budgets=[600], seed=8, decode_steps=20)
+    outs = []
+    for _ in range(2):
+        dc = U.DeviceCase(case, decode_cap=21, reprune=True)
+        dc.layer.prune(dc.q_win, dc.k, dc.v, dc.modality)
+        for t in range(20):
+            _decode_and_check(U, oracle, dc, case, t, [])
+        dc.layer.reprune()
+        torch.cuda.synchronize()
+        s = _snapshot(U, dc.layer, "bf16")
+        outs.append((s["k"][:, :, :600].copy(), s["mod"].copy(), dc.layer.rp_self.cpu().numpy()[:, :, :604].copy()))
+    np.testing.assert_array_equal(outs[0][0], outs[1][0])
+    np.testing.assert_array_equal(outs[0][1], outs[1][1])
+    np.testing.assert_array_equal(outs[0][2], outs[1][2])
