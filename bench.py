@@ -223,6 +223,50 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
     return res
 
 
+def measure_reprune(cfg, inputs, budget_frac, period, cycles, device):
+    """Re-pruning while decoding: every layer is pruned after prefill, then `cycles` times: `period`
+    decode steps (append + attend + window push, one call) followed by csp_reprune on every layer (cache
+    T + period -> T).  Times one csp_reprune call per layer and the decode steps between them."""
+    import torch
+    from paper_2412_04652_amd.runner import CspLayer
+    T = int(cfg["L"] * budget_frac)
+    B, H, D, O = cfg["B"], cfg["H"], cfg["D"], cfg["O"]
+    layers = [CspLayer(dtype="bf16", H_q=H, H_kv=H, D=D, O=O, R=O, cu_seqlens=inp["cu"], budgets=[T] * B,
+                       decode_cap=period, device=device, reprune=True) for inp in inputs]
+    g = torch.Generator(device=device); g.manual_seed(778)
+    dq, dk, dv = (torch.randn((B, H, D), generator=g, device=device).to(torch.bfloat16) for _ in range(3))
+    for inp, lay in zip(inputs, layers):
+        lay.prune(inp["q"], inp["k"], inp["v"], inp["mod"])
+    rp_ms, dec_ms = [], []
+    for c in range(cycles + 1):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for t in range(period):
+            for lay in layers:
+                lay.decode_step_window(dq, dk, dv)
+        b.record()
+        pairs = []
+        for lay in layers:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); lay.reprune(); e1.record()
+            pairs.append((e0, e1))
+        torch.cuda.synchronize()
+        if c > 0:  # first cycle warms up
+            rp_ms += [x.elapsed_time(y) for x, y in pairs]
+            dec_ms.append(a.elapsed_time(b))
+    kept = float(torch.stack([l.kv_len.float().mean() for l in layers]).mean())
+    e = 2
+    rp = sum(rp_ms) / len(rp_ms)
+    step = sum(dec_ms) / len(dec_ms) / period / len(layers)
+    # keys of the grown cache read for scoring + kept K/V rows read and written by the compaction
+    by = B * H * ((T + period) * D * e + 4 * T * D * e)
+    del layers
+    torch.cuda.empty_cache()
+    return dict(budget=budget_frac, T=T, period=period, layers=len(inputs), reprune_ms_per_layer=rp,
+                reprune_gbps=by / (rp * 1e-3) / 1e9, bytes=by, decode_step_ms_per_layer=step,
+                share_of_decode_time=rp / (rp + period * step), kv_len_after=kept)
+
+
 def copy_peak(device):
     """Plain device-to-device copy of 2 GiB: the achievable stream bandwidth on this machine."""
     import torch
@@ -327,6 +371,9 @@ def main():
         variants["mixed_window_48v_16t"]["kernels"] = r["kernels"]
         del mixed
         torch.cuda.empty_cache()
+    reprune = None
+    if not args.no_variants and args.workload == "7b_16k" and args.sel_group == 1:
+        reprune = measure_reprune(cfg, inputs[:8], args.budget, cfg["O"], 2, device)
     peak_copy = copy_peak(device)
     cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds)
 
@@ -371,6 +418,8 @@ def main():
         out["second_budget"]["kernels"] = second["kernels"]
     if variants is not None:
         out["variants_8_layers"] = variants
+    if reprune is not None:
+        out["reprune_while_decoding_8_layers"] = reprune
     if head_avg is not None:
         out["head_averaged"] = {k: head_avg[k] for k in ("budget", "T", "sel_group", "prune_ms", "tokens_per_s", "prune_gbps")}
         out["head_averaged"]["kernels"] = head_avg["kernels"]

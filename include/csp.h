@@ -265,6 +265,12 @@ int csp_append_kv(const csp_desc* desc, const void* k_new, const void* v_new, vo
  * K, V and mod_cache must not be accessed by other work until the call's
  * kernels have finished.
  * ---------------------------------------------------------------------- */
+/* csp_decode_step_window — csp_decode_step that also does csp_window_push(q, q_ring, slot)
+ * inside its first kernel (no extra launch per decode step). */
+int csp_decode_step_window(const csp_desc* desc, const void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
+                           int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, float* out,
+                           void* q_ring, int32_t slot, void* ws, size_t ws_bytes, void* stream);
 int csp_gather_modality(const csp_desc* desc, const uint8_t* modality, const int32_t* kept_idx,
                         int32_t kept_cap, const int32_t* kept_cnt, uint8_t* mod_cache,
                         int32_t cache_cap, void* stream);

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "csp_compact",
     "csp_decode_workspace_bytes", "csp_decode_attn", "csp_decode_step", "csp_decode_step_phase",
     "csp_append_kv",
-    "csp_gather_modality", "csp_window_push", "csp_reprune_workspace_bytes", "csp_reprune",
+    "csp_gather_modality", "csp_window_push", "csp_decode_step_window", "csp_reprune_workspace_bytes", "csp_reprune",
 ]
 
 
@@ -70,6 +70,8 @@ def load_library():
         L.csp_append_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]; L.csp_append_kv.restype = C.c_int
         L.csp_gather_modality.argtypes = [dp, vp, vp, i32, vp, vp, i32, vp]; L.csp_gather_modality.restype = C.c_int
         L.csp_window_push.argtypes = [dp, vp, vp, i32, vp]; L.csp_window_push.restype = C.c_int
+        L.csp_decode_step_window.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, i32, vp, sz, vp]
+        L.csp_decode_step_window.restype = C.c_int
         L.csp_reprune_workspace_bytes.argtypes = [dp, i32]; L.csp_reprune_workspace_bytes.restype = sz
         L.csp_reprune.argtypes = [dp, vp, i32, vp, vp, i64, i64, i64, i32, vp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.csp_reprune.restype = C.c_int
@@ -223,3 +225,11 @@ def csp_reprune(desc: Desc, q_ring, ring_start: int, k_cache, v_cache, cache_str
                                       int(cache_strides[0]), int(cache_strides[1]), int(cache_strides[2]), int(cache_cap),
                                       _ptr(mod_cache), _ptr(kv_len), _ptr(score_self), _ptr(score_cross), _ptr(kept_idx),
                                       int(kept_cap), _ptr(kept_cnt), _ptr(ws), _nbytes(ws), _stream(stream)), "csp_reprune")
+
+
+def csp_decode_step_window(desc: Desc, q, k_new, v_new, k_cache, v_cache, cache_strides, cache_cap: int, kv_len, out,
+                           q_ring, slot: int, ws, stream=None) -> None:
+    _check(load_library().csp_decode_step_window(desc.ref(), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_cache), _ptr(v_cache),
+                                                 int(cache_strides[0]), int(cache_strides[1]), int(cache_strides[2]),
+                                                 int(cache_cap), _ptr(kv_len), _ptr(out), _ptr(q_ring), int(slot), _ptr(ws),
+                                                 _nbytes(ws), _stream(stream)), "csp_decode_step_window")

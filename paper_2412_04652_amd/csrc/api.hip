@@ -195,11 +195,13 @@ size_t csp_decode_workspace_bytes(const csp_desc* d, int32_t max_kv_len) {
 static int decode_common(const csp_desc* d, const void* q, const void* k_new, const void* v_new,
                          void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
                          int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, int32_t max_kv_len,
-                         float* out, void* ws, size_t ws_bytes, void* stream, int phases = 3) {
+                         float* out, void* ws, size_t ws_bytes, void* stream, int phases = 3,
+                         void* q_ring = nullptr, int32_t ring_slot = 0) {
     Checked c;
     int rc = check_desc(d, false, &c);
     if (rc != CSP_OK) return rc;
     if (!q || !k_cache || !v_cache || !kv_len || !out || max_kv_len <= 0) return CSP_EINVAL;
+    if (q_ring && (!aligned16(q_ring) || d->window_O <= 0 || ring_slot < 0 || ring_slot >= d->window_O)) return CSP_EINVAL;
     if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return CSP_EINVAL;
     if (k_new && (!v_new || !aligned16(k_new) || !aligned16(v_new) || cache_cap <= 0)) return CSP_EINVAL;
     if ((rc = check_kv_strides(cache_stride_tok, cache_stride_head, d->D, c.EB)) != CSP_OK) return rc;
@@ -210,6 +212,7 @@ static int decode_common(const csp_desc* d, const void* q, const void* k_new, co
     std::memset(&p, 0, sizeof(p));
     p.q = q; p.k_new = k_new; p.v_new = v_new; p.k_cache = k_cache; p.v_cache = v_cache; p.kv_len = kv_len; p.out = out;
     p.cache_cap = cache_cap;
+    p.q_ring = q_ring; p.ring_O = d->window_O; p.ring_slot = ring_slot;
     p.phases = phases;
     p.part = static_cast<float*>(ws);
     p.B = d->B; p.H_q = d->H_q; p.H_kv = d->H_kv; p.G = c.G;
@@ -237,6 +240,15 @@ int csp_decode_step(const csp_desc* d, const void* q, const void* k_new, const v
     if (!k_new || !v_new) return CSP_EINVAL;
     return decode_common(d, q, k_new, v_new, k_cache, v_cache, cache_stride_b, cache_stride_head, cache_stride_tok,
                          cache_cap, kv_len, cache_cap, out, ws, ws_bytes, stream);
+}
+
+int csp_decode_step_window(const csp_desc* d, const void* q, const void* k_new, const void* v_new, void* k_cache,
+                           void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                           int32_t cache_cap, int32_t* kv_len, float* out, void* q_ring, int32_t slot, void* ws,
+                           size_t ws_bytes, void* stream) {
+    if (!k_new || !v_new || !q_ring) return CSP_EINVAL;
+    return decode_common(d, q, k_new, v_new, k_cache, v_cache, cache_stride_b, cache_stride_head, cache_stride_tok,
+                         cache_cap, kv_len, cache_cap, out, ws, ws_bytes, stream, 3, q_ring, slot);
 }
 
 int csp_decode_step_phase(const csp_desc* d, int32_t phase, const void* q, const void* k_new, const void* v_new,

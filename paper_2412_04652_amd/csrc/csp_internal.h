@@ -130,6 +130,8 @@ struct DecodeParams {
     void* v_cache;
     int32_t* kv_len;
     int32_t cache_cap;
+    void* q_ring;         // ring of the last ring_O queries [B][H_q][ring_O][D]; nullptr = not recorded
+    int32_t ring_O, ring_slot;
     int32_t phases;       // bit 0: split kernel, bit 1: merge kernel
     float* out;
     float* part;          // [B][H_q][n_splits][D + 2]

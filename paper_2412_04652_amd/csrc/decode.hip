@@ -83,6 +83,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_split_kernel(DecodeParams 
             const int hq = hk * p.G + g0 + g;
             u32x4 w = {0u, 0u, 0u, 0u};
             if (g0 + g < p.G) w = *reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(p.q) + ((size_t)(b * p.H_q + hq) * D) * EB + sl * 16);
+            // the step's query goes into the window ring on the way (one workgroup per head does it)
+            if (p.q_ring != nullptr && split == 0 && wave == 0 && sub == 0 && g0 + g < p.G)
+                *reinterpret_cast<u32x4*>(reinterpret_cast<char*>(p.q_ring) +
+                                          (((size_t)(b * p.H_q + hq) * p.ring_O + p.ring_slot) * D) * EB + sl * 16) = w;
             Unpack<E>::run(w, q[g]);
 #pragma unroll
             for (int e = 0; e < EPL; ++e) { q[g][e] *= p.scale_log2; o[g][e] = 0.f; }

@@ -108,6 +108,14 @@ class CspLayer:
         B_.csp_window_push(self.desc, q, self.q_ring, self.pushes % self.O, stream)
         self.pushes += 1
 
+    def decode_step_window(self, q, k_new, v_new, stream=None, out: Optional[torch.Tensor] = None):
+        """decode_step + push_query in the same launches"""
+        o = self.out if out is None else out
+        B_.csp_decode_step_window(self.desc, q, k_new, v_new, self.k_cache, self.v_cache, self.cache_strides,
+                                  self.cache_cap, self.kv_len, o, self.q_ring, self.pushes % self.O, self.ws_decode, stream)
+        self.pushes += 1
+        return o
+
     def reprune(self, stream=None):
         """prunes the grown cache in place (sequences within their budget are left alone)"""
         B_.csp_reprune(self.desc, self.q_ring, self.pushes % self.O, self.k_cache, self.v_cache, self.cache_strides,

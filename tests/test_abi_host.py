@@ -110,6 +110,39 @@ def test_budget_below_recent_is_rejected(P):
     assert d.c.budget_T_host is not None
 
 
+def test_reprune_validation(P):
+    L = P.load_library()
+    d = _desc(P)
+    cap = 2048 + 64
+    sb, sh, st = 8 * cap * 128, cap * 128, 128
+    ws = P.csp_reprune_workspace_bytes(d, cap)
+    # ordered window (2*8*64 rows of 256 bytes) + softmax statistics per chunk; no slices for sel_group 1
+    n_chunks = -(-cap // 128)
+    assert ws == 2 * 8 * 64 * 256 + 2 * 8 * n_chunks * 64 * 2 * 4
+    dg = _desc(P, H_q=32, H_kv=8, sel_group=4, B=1, cu_seqlens_host=[0, 4096], budget_T_host=[2048])
+    assert P.csp_reprune_workspace_bytes(dg, cap) > 1 * 32 * 64 * 256 + 2 * 4 * 1 * 8 * cap * 4   # slices of the group
+
+    def call(desc=d, ring=FAKE, start=0, k=FAKE, s_tok=st, mod=FAKE, kept_cap=2048, wsp=FAKE, wsb=1 << 30):
+        return L.csp_reprune(desc.ref(), ring, start, k, FAKE, sb, sh, s_tok, cap, mod, FAKE, FAKE, FAKE, FAKE, kept_cap,
+                             FAKE, wsp, wsb, None)
+
+    assert call(ring=None) == -1
+    assert call(mod=None) == -1
+    assert call(start=64) == -1 and call(start=-1) == -1
+    assert call(k=FAKE + 8) == -1
+    assert call(s_tok=100) == -1
+    assert call(kept_cap=2047) == -1                                   # below a budget
+    assert call(desc=_desc(P, budget_T_host=[32, 2048])) == -1          # budget below the window
+    assert call(desc=_desc(P, budget_T=None)) == -1
+    assert call(wsp=None) == -3 and call(wsb=ws - 1) == -3
+    assert call(desc=_desc(P, window_O=200, recent_R=64)) == -2
+    # companions
+    assert L.csp_window_push(d.ref(), FAKE, FAKE, 64, None) == -1
+    assert L.csp_window_push(d.ref(), None, FAKE, 0, None) == -1
+    assert L.csp_gather_modality(d.ref(), FAKE, FAKE, 2048, FAKE, None, cap, None) == -1
+    assert L.csp_gather_modality(d.ref(), FAKE, FAKE, 0, FAKE, FAKE, cap, None) == -1
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, P):
     import paper_2412_04652_amd.binding as b
     monkeypatch.setattr(b, "_lib", None)

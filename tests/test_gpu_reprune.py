@@ -94,8 +94,11 @@ def _decode_and_check(U, oracle, dc, case, t, sample_heads):
     dq = U.to_dev(case.dec_q[t], case.dtype)
     dk = U.to_dev(case.dec_k[t], case.dtype)
     dv = U.to_dev(case.dec_v[t], case.dtype)
-    lay.decode_step(dq, dk, dv)
-    lay.push_query(dq)
+    if t % 2 == 0:  # the ring push fused into the decode launch, or as a call of its own
+        lay.decode_step_window(dq, dk, dv)
+    else:
+        lay.decode_step(dq, dk, dv)
+        lay.push_query(dq)
     if not sample_heads:
         return
     torch.cuda.synchronize()
@@ -210,3 +213,58 @@ def test_reprune_deterministic(gpu, oracle):
     np.testing.assert_array_equal(outs[0][0], outs[1][0])
     np.testing.assert_array_equal(outs[0][1], outs[1][1])
     np.testing.assert_array_equal(outs[0][2], outs[1][2])
+
+
+def test_reprune_7b_16k_layer_sampled(gpu, oracle):
+    """One layer of the benchmark workload (B=4, 32 heads, L=16384, D=128, window 64, T=8192): pruned after
+    prefill, 64 decode steps (the window then holds decode queries only), re-pruned in place;
+    sampled (sequence, head) problems are checked against the oracle, the rest by properties."""
+    U = _util()
+    from paper_2412_04652_amd.runner import CspLayer
+    rng = np.random.default_rng(1000)
+    layouts = [W.layout_7b_16k(rng) for _ in range(4)]
+    H, D, O, T, S = 32, 128, 64, 8192, 64
+    q, k, v, mod, cu_dev, cu = W.device_qkv(layouts, H_q=H, H_kv=H, D=D, O=O, seed=0, device=gpu)
+    lay = CspLayer(dtype="bf16", H_q=H, H_kv=H, D=D, O=O, R=O, cu_seqlens=cu.tolist(), budgets=[T] * 4, decode_cap=S,
+                   device=gpu, reprune=True)
+    print("[reprune] 7b_16k layer", flush=True)
+    lay.prune(q, k, v, mod)
+    g = torch.Generator(device=gpu); g.manual_seed(4242)
+    dqs = []
+    for t in range(S):
+        dq = torch.randn((4, H, D), generator=g, device=gpu).to(torch.bfloat16)
+        dk = torch.randn((4, H, D), generator=g, device=gpu).to(torch.bfloat16)
+        dv = torch.randn((4, H, D), generator=g, device=gpu).to(torch.bfloat16)
+        lay.decode_step_window(dq, dk, dv)
+        dqs.append(dq)
+    torch.cuda.synchronize()
+    assert (lay.kv_len == T + S).all()
+    before = _snapshot(U, lay, "bf16")
+    window = U.from_dev_bits(torch.stack(dqs, dim=2), "bf16")   # [B][H][64][D], temporal order
+    lay.reprune()
+    torch.cuda.synchronize()
+    nd = _check_reprune(U, oracle, lay, before, window, dtype="bf16", H_q=H, H_kv=H, sel_group=1, O=O, R=O,
+                        budgets=[T] * 4, n_score=0.0, cross_ratio=0.5, sample=[(0, 0), (1, 13), (3, 31)], what="7b_16k")
+    print(f"[reprune] keys differing near the threshold: {nd}", flush=True)
+    assert nd <= 12
+    after = _snapshot(U, lay, "bf16")
+    assert (after["kv_len"] == T).all()
+    cnt, idx = lay.rp_cnt.cpu().numpy(), lay.rp_idx.cpu().numpy()
+    assert (cnt[:, :, 0] == T).all() and (cnt[:, :, 1] + cnt[:, :, 2] == T - O).all()
+    assert (np.diff(idx, axis=-1) > 0).all() and (idx[:, :, -O:] == np.arange(T + S - O, T + S)).all()
+    # every head: the new cache is the gather of the old one at the kept positions (checked on the device)
+    kc_before = torch.from_numpy(before["k"].view(np.int16)).to(gpu)
+    gathered = torch.gather(kc_before[:, :, :, :8].long(), 2, lay.rp_idx.long().unsqueeze(-1).expand(-1, -1, -1, 8))
+    assert torch.equal(gathered, lay.k_cache[:, :, :T, :8].view(torch.int16).long())
+    # and the cache keeps working: one more decode step against the oracle
+    dq = torch.randn((4, H, D), generator=g, device=gpu).to(torch.bfloat16)
+    dk = torch.randn((4, H, D), generator=g, device=gpu).to(torch.bfloat16)
+    dv = torch.randn((4, H, D), generator=g, device=gpu).to(torch.bfloat16)
+    lay.decode_step(dq, dk, dv)
+    torch.cuda.synchronize()
+    out = lay.out.cpu().numpy()
+    kc, vc = U.from_dev_bits(lay.k_cache, "bf16"), U.from_dev_bits(lay.v_cache, "bf16")
+    for b, h in [(0, 0), (2, 17)]:
+        ref = oracle.decode(oracle.bf16_bits_to_f64(U.from_dev_bits(dq[b, h], "bf16")), oracle.bf16_bits_to_f64(kc[b, h, :T + 1]),
+                            oracle.bf16_bits_to_f64(vc[b, h, :T + 1]), 1.0)
+        U.assert_decode_close(out[b, h], ref, f"decode after reprune b{b} h{h}")
