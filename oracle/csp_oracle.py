@@ -209,3 +209,22 @@ def prune_group(case, b: int, s: int, scores=None, combine: str = "union"):
         scores = group_scores(case, b, s) if L > T else (np.zeros(L), np.zeros(L))
     idx, cnt = select(scores[0], scores[1], mod, case.O, case.R, T, case.cross_ratio, combine)
     return {"a_self": scores[0], "a_cross": scores[1], "idx": idx, "counts": cnt}
+
+
+def reprune_group(windows, keys, mod, O: int, R: int, T: int, cross_ratio: float = 0.5, n_score: float = 0.0,
+                  causal: bool = True):
+    """The body of Algorithm 1's generation loop for one (sequence, selection group) whose cache
+    holds L keys: early-out when L <= T, otherwise the scores of the last O queries against the
+    cached keys (in cache order, which is temporal order; window row i sees cache rows
+    t <= L-O+i), summed over the group's heads, then the same selection as after prefill.
+    windows: per query head of the group, the last O queries [O,D], oldest first;
+    keys: per query head, the cached keys of its KV head [L,D]; mod: uint8[L], modality flag of
+    every cached key (0 for tokens appended while decoding).  Returns dict as prune_group."""
+    mod = np.ascontiguousarray(mod, dtype=np.uint8)
+    L = mod.shape[0]
+    a_s, a_c = np.zeros(L), np.zeros(L)
+    if L > T:
+        for q, k in zip(windows, keys):
+            head_scores(q, k, mod, R, n_score, causal, a_s, a_c)
+    idx, cnt = select(a_s, a_c, mod, O, R, T, cross_ratio)
+    return {"a_self": a_s, "a_cross": a_c, "idx": idx, "counts": cnt}

@@ -59,14 +59,14 @@ def _check_reprune(U, oracle, lay, before, window, *, dtype, H_q, H_kv, sel_grou
             assert cnt_all[b, s, 0] == L and (idx_all[b, s, :L] == np.arange(L)).all()
             continue
         m = before["mod"][b, s, :L]
-        a_s, a_c = np.zeros(L), np.zeros(L)
-        for hq in range(s * sel_group, (s + 1) * sel_group):
-            oracle.head_scores(_f64(oracle, window[b, hq], dtype), _f64(oracle, before["k"][b, hq // G, :L], dtype),
-                               m, R, n_score, True, a_s, a_c)
+        heads = range(s * sel_group, (s + 1) * sel_group)
+        res = oracle.reprune_group([_f64(oracle, window[b, hq], dtype) for hq in heads],
+                                   [_f64(oracle, before["k"][b, hq // G, :L], dtype) for hq in heads],
+                                   m, O, R, T, cross_ratio, n_score)
+        a_s, a_c, ref_idx, rc = res["a_self"], res["a_cross"], res["idx"], res["counts"]
         P = L - R
         U.assert_scores_close(g_self[b, s, :P], a_s[:P], f"{what} b{b} s{s} self")
         U.assert_scores_close(g_cross[b, s, :P], a_c[:P], f"{what} b{b} s{s} cross")
-        ref_idx, rc = oracle.select(a_s, a_c, m, O, R, T, cross_ratio)
         n = int(cnt_all[b, s, 0])
         assert cnt_all[b, s, 1:3].tolist() == [rc["K_s"], rc["K_c"]]
         gi = idx_all[b, s, :n]
