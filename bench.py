@@ -217,6 +217,8 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
         call_ms = avg(ms["decode_split"])
         res.update(decode_ms_per_token=dec_ms / decode_steps,
                    decode_gbps=by_decode * n_layers * decode_steps / (dec_ms * 1e-3) / 1e9)
+        # the whole step: algorithmic bytes of both phases over the sum of their event times
+        res["step_gbps"] = n_layers * (by_score + by_select + by_compact + by_decode * decode_steps) / ((prune_ms + dec_ms) * 1e-3) / 1e9
         res["kernels"]["decode_split"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
     del layers
     torch.cuda.empty_cache()
@@ -407,6 +409,8 @@ def main():
         "decode_attn_hbm_gbps": main_res.get("decode_gbps"),
         "decode_frac_of_peak": (main_res.get("decode_gbps") or 0.0) / HBM_PEAK_GBPS,
         "decode_ms_per_token_all_layers": main_res.get("decode_ms_per_token"),
+        "step_hbm_gbps": main_res.get("step_gbps"),
+        "step_frac_of_peak": (main_res.get("step_gbps") or 0.0) / HBM_PEAK_GBPS,
         "copy_peak_gbps": peak_copy,
         "kernels": kern,
         "roofline": roof,
