@@ -635,20 +635,23 @@ hipError_t launch_nqb(const ScoreParams& p, hipStream_t s) {
 
 }  // namespace
 
+#ifndef CSP_SCORE_MIN_TASKS
+#define CSP_SCORE_MIN_TASKS 512
+#endif
 int score_chunk_keys(int B, int H_q, int max_seqlen) {
-    // largest chunk that still gives every compute unit about four workgroups (two resident at a
-    // time): long chunks amortise the per-head set-up of a workgroup
+    // largest chunk that still gives every compute unit two workgroups (one resident set, no
+    // second round with a ragged tail): long chunks amortise the per-head set-up of a workgroup
     int ck = 4096;
-    while (ck > 128 && (int64_t)B * H_q * ((max_seqlen + ck - 1) / ck) < 1024) ck >>= 1;
+    while (ck > 128 && (int64_t)B * H_q * ((max_seqlen + ck - 1) / ck) < CSP_SCORE_MIN_TASKS) ck >>= 1;
     return ck;
 }
 
 int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks) {
-    // one workgroup sums a whole group while that still leaves about four workgroups per compute
-    // unit; larger groups are cut into equal slices
+    // one workgroup sums a whole group while that still leaves two workgroups per compute unit;
+    // larger groups are cut into equal slices
     const int64_t groups = (int64_t)B * (H_q / sel_group) * n_chunks;
     int gper = sel_group;
-    while (gper > 1 && groups * ((sel_group + gper - 1) / gper) < 1024) gper = (gper + 1) / 2;
+    while (gper > 1 && groups * ((sel_group + gper - 1) / gper) < CSP_SCORE_MIN_TASKS) gper = (gper + 1) / 2;
     return gper;
 }
 
