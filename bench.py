@@ -87,6 +87,36 @@ def make_layers(cfg, inputs, budget_frac, decode_steps, device, sel_group=1, cro
             for inp in inputs], T
 
 
+def with_row_lse(cfg, inputs):
+    """Copies of the inputs that carry the log-sum-exp of every window row (what the prefill
+    attention of the layer would hand over), computed here with torch outside any timed region."""
+    import torch
+    out = []
+    O, D = cfg["O"], cfg["D"]
+    for inp in inputs:
+        cu = inp["cu"]
+        lse = torch.empty((cfg["B"], cfg["H"], O), dtype=torch.float32, device=inp["q"].device)
+        for b in range(cfg["B"]):
+            lo, hi = cu[b], cu[b + 1]
+            L = hi - lo
+            S = torch.matmul(inp["q"][b].float(), inp["k"][:, lo:hi].float().transpose(1, 2)) / (D ** 0.5)  # [H, O, L]
+            pos = torch.arange(L - O, L, device=S.device)[:, None]
+            S.masked_fill_(torch.arange(L, device=S.device)[None, :] > pos, float("-inf"))
+            lse[b] = torch.logsumexp(S, dim=-1)
+            del S
+        d = dict(inp)
+        d["lse"] = lse
+        out.append(d)
+    return out
+
+
+def _score(lay, inp):
+    if "lse" in inp:
+        lay.score_lse(inp["q"], inp["k"], inp["mod"], inp["lse"])
+    else:
+        lay.score(inp["q"], inp["k"], inp["mod"])
+
+
 class Timer:
     """HIP events on torch's current stream (the stream every kernel here is launched on)."""
 
@@ -118,7 +148,7 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, stre
             n_call += 1
             if sampled:
                 e0, e1 = timer.span("score"); e0.record()
-            lay.score(inp["q"], inp["k"], inp["mod"])
+            _score(lay, inp)
             if sampled:
                 e1.record(); e2, e3 = timer.span("select"); e2.record()
             lay.select(inp["mod"])
@@ -135,7 +165,7 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, stre
             s.wait_stream(main)
         for li, (inp, lay) in enumerate(zip(inputs, layers)):
             with torch.cuda.stream(streams[li % len(streams)]):
-                lay.score(inp["q"], inp["k"], inp["mod"])
+                _score(lay, inp)
                 lay.select(inp["mod"])
                 lay.compact(inp["k"], inp["v"])
         for s in streams:
@@ -367,6 +397,10 @@ def main():
         for ratio in (0.0, 0.25, 0.75, 1.0):
             r = measure(cfg, sub, args.budget, 0, 2, 1, device, args.streams, cross_ratio=ratio)
             variants[f"cross_ratio_{ratio:g}"] = {k: r[k] for k in keys}
+        # the window rows' normalisers supplied by the caller (csp_score_lse): the keys are read once
+        r = measure(cfg, with_row_lse(cfg, sub), args.budget, 0, 2, 1, device, args.streams)
+        variants["row_lse_supplied"] = {k: r[k] for k in keys}
+        variants["row_lse_supplied"]["kernels"] = r["kernels"]
         mixed = build_inputs(cfg, 8, device, window_text=16)
         r = measure(cfg, mixed, args.budget, 0, 2, 1, device, args.streams)
         variants["mixed_window_48v_16t"] = {k: r[k] for k in keys}

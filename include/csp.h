@@ -118,6 +118,24 @@ int csp_score(const csp_desc* desc, const void* q_win, const void* k, const uint
               float* score_self, float* score_cross, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * csp_score_lse — csp_score for callers that already hold the softmax
+ * normaliser of every window row: the prefill attention of the same layer
+ * computes, per query row, the log-sum-exp of its scaled logits, and the
+ * statistics half of csp_score would only recompute it from a second pass
+ * over the keys.
+ *   row_lse   device float [B][H_q][O]: ln( sum over visible keys j of
+ *             exp(q_i.k_j / sqrt(D)) ) for window row i (causal: j <= L-O+i;
+ *             all keys when desc->causal == 0), WITHOUT the n of the n-softmax
+ *             (n_score is added here)
+ * Everything else as in csp_score (same workspace size; the keys are read
+ * once instead of twice).  The result equals csp_score's up to the rounding
+ * of row_lse.
+ * ---------------------------------------------------------------------- */
+int csp_score_lse(const csp_desc* desc, const void* q_win, const void* k, const uint8_t* modality,
+                  const float* row_lse, float* score_self, float* score_cross,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
  * csp_select — Eq. "top-K" per region, the mask combination (read as the
  * union of the two independently selected sets), the recent keys of the
  * cache-construction equation, and Algorithm 1's early-out.

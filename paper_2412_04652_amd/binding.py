@@ -13,7 +13,7 @@ CSP_BF16, CSP_F32 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "csp_strerror", "csp_version",
-    "csp_score_workspace_bytes", "csp_score",
+    "csp_score_workspace_bytes", "csp_score", "csp_score_lse",
     "csp_select_workspace_bytes", "csp_select",
     "csp_compact",
     "csp_decode_workspace_bytes", "csp_decode_attn", "csp_decode_step", "csp_decode_step_phase",
@@ -62,6 +62,7 @@ def load_library():
         L.csp_select_workspace_bytes.argtypes = [dp]; L.csp_select_workspace_bytes.restype = sz
         L.csp_decode_workspace_bytes.argtypes = [dp, i32]; L.csp_decode_workspace_bytes.restype = sz
         L.csp_score.argtypes = [dp, vp, vp, vp, vp, vp, vp, sz, vp]; L.csp_score.restype = C.c_int
+        L.csp_score_lse.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]; L.csp_score_lse.restype = C.c_int
         L.csp_select.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]; L.csp_select.restype = C.c_int
         L.csp_compact.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, vp, vp]; L.csp_compact.restype = C.c_int
         L.csp_decode_attn.argtypes = [dp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, sz, vp]; L.csp_decode_attn.restype = C.c_int
@@ -157,6 +158,11 @@ def csp_decode_workspace_bytes(desc: Desc, max_kv_len: int) -> int:
 def csp_score(desc: Desc, q_win, k, modality, score_self, score_cross, ws, stream=None) -> None:
     _check(load_library().csp_score(desc.ref(), _ptr(q_win), _ptr(k), _ptr(modality), _ptr(score_self),
                                     _ptr(score_cross), _ptr(ws), _nbytes(ws), _stream(stream)), "csp_score")
+
+
+def csp_score_lse(desc: Desc, q_win, k, modality, row_lse, score_self, score_cross, ws, stream=None) -> None:
+    _check(load_library().csp_score_lse(desc.ref(), _ptr(q_win), _ptr(k), _ptr(modality), _ptr(row_lse), _ptr(score_self),
+                                        _ptr(score_cross), _ptr(ws), _nbytes(ws), _stream(stream)), "csp_score_lse")
 
 
 def csp_select(desc: Desc, score_self, score_cross, modality, kept_idx, kept_cap: int, kept_cnt,

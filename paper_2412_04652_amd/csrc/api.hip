@@ -106,8 +106,9 @@ size_t csp_score_workspace_bytes(const csp_desc* d) {
     return bytes;
 }
 
-int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t* modality,
-              float* score_self, float* score_cross, void* ws, size_t ws_bytes, void* stream) {
+static int score_common(const csp_desc* d, const void* q_win, const void* k, const uint8_t* modality,
+                        const float* row_lse, float* score_self, float* score_cross, void* ws, size_t ws_bytes,
+                        void* stream) {
     Checked c;
     int rc = check_desc(d, true, &c);
     if (rc != CSP_OK) return rc;
@@ -122,6 +123,7 @@ int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t
     p.q_win = q_win; p.k = k; p.modality = modality;
     p.score_self = score_self; p.score_cross = score_cross;
     p.part = static_cast<float*>(ws);
+    p.row_lse = row_lse;
     p.view.cu = d->cu_seqlens; p.view.H_kv = d->H_kv; p.view.H_sel = c.H_sel; p.view.total_tokens = c.total_tokens;
     p.score_elems = (int64_t)c.H_sel * c.total_tokens;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
@@ -139,6 +141,17 @@ int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
     p.n_score = (float)d->n_score;
     return launch_score(p, d->dtype, d->D, d->max_seqlen, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
+int csp_score(const csp_desc* d, const void* q_win, const void* k, const uint8_t* modality,
+              float* score_self, float* score_cross, void* ws, size_t ws_bytes, void* stream) {
+    return score_common(d, q_win, k, modality, nullptr, score_self, score_cross, ws, ws_bytes, stream);
+}
+
+int csp_score_lse(const csp_desc* d, const void* q_win, const void* k, const uint8_t* modality, const float* row_lse,
+                  float* score_self, float* score_cross, void* ws, size_t ws_bytes, void* stream) {
+    if (!row_lse) return CSP_EINVAL;
+    return score_common(d, q_win, k, modality, row_lse, score_self, score_cross, ws, ws_bytes, stream);
 }
 
 size_t csp_select_workspace_bytes(const csp_desc*) { return 0; }

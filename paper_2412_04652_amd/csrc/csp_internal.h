@@ -74,6 +74,8 @@ struct ScoreParams {
     float* score_self;
     float* score_cross;
     float* part;          // [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units
+    const float* row_lse; // [B][H_q][O] natural-log normaliser of every window row, supplied by the caller
+                          // (then the statistics pass is skipped and `part` is not used); nullptr otherwise
     float* slice_self;    // [gsplit][score_elems] per-slice sums of a split selection group (gsplit > 1)
     float* slice_cross;
     SeqView view;

@@ -495,7 +495,12 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
         __syncthreads();  // previous head's nlse_s / q_lds are no longer read
         if (tid < NQB * 32) {
             float nl = NEG_INF;
-            if (tid < O) {
+            if (tid < O && p.row_lse != nullptr) {
+                // the caller's log-sum-exp of the scaled logits (natural log), e.g. from the prefill
+                // attention kernel; the n of the n-softmax is added to the row sum here
+                const float l2 = p.row_lse[(size_t)(b * p.H_q + hq) * O + tid] * 1.44269504088896340736f;
+                nl = -(p.n_score > 0.f ? l2 + fast_log2(1.f + p.n_score * fast_exp2(-l2)) : l2) / c;
+            } else if (tid < O) {
                 const float2* part = reinterpret_cast<const float2*>(p.part) + ((size_t)(b * p.H_q + hq) * p.n_chunks) * O + tid;
                 // merge of the chunk partials (max, sum): 8 independent loads at a time
                 float M = NEG_INF, Ls = 0.f;
@@ -615,9 +620,12 @@ hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
     const dim3 block(kThreads);
     const dim3 grid_a(p.n_chunks, p.H_q, p.B);
     const dim3 grid_b(p.n_chunks, (p.H_q / p.sel_group) * p.gsplit, p.B);
-    hipLaunchKernelGGL(ka, grid_a, block, smem_a, s, p);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (p.row_lse == nullptr) {  // the row normalisers are not given: first pass over the keys
+        hipLaunchKernelGGL(ka, grid_a, block, smem_a, s, p);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(kb, grid_b, block, smem_b, s, p);
     e = hipGetLastError();
     if (e != hipSuccess || p.gsplit == 1) return e;

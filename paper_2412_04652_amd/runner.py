@@ -79,6 +79,10 @@ class CspLayer:
     def score(self, q_win, k, modality, stream=None):
         B_.csp_score(self.desc, q_win, k, modality, self.score_self, self.score_cross, self.ws_score, stream)
 
+    def score_lse(self, q_win, k, modality, row_lse, stream=None):
+        """score with the window rows' log-sum-exp supplied (the keys are read once)"""
+        B_.csp_score_lse(self.desc, q_win, k, modality, row_lse, self.score_self, self.score_cross, self.ws_score, stream)
+
     def select(self, modality, stream=None, score_self=None, score_cross=None):
         B_.csp_select(self.desc, self.score_self if score_self is None else score_self,
                       self.score_cross if score_cross is None else score_cross, modality,

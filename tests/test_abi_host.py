@@ -91,6 +91,8 @@ def test_null_pointers_and_workspace(P):
     assert L.csp_score(d.ref(), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == -3
     assert L.csp_score(d.ref(), FAKE + 4, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == -1   # misaligned q
     assert L.csp_score(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert L.csp_score_lse(d.ref(), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, 1 << 30, None) == -1
+    assert L.csp_score_lse(d.ref(), FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 16, None) == -3
     assert L.csp_select(d.ref(), FAKE, FAKE, FAKE, None, 2048, FAKE, None, 0, None) == -1
     assert L.csp_select(d.ref(), FAKE, FAKE, FAKE, FAKE, 100, FAKE, None, 0, None) == -1       # kept_cap < min(T, L)
     assert L.csp_compact(d.ref(), FAKE, FAKE, FAKE, 2048, FAKE, FAKE, None, 1, 1, 128, None, None) == -1

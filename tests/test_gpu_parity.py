@@ -85,6 +85,54 @@ def test_score_matches_oracle(gpu, oracle, name):
             assert not g_self[s, lo + P:hi].any() and not g_cross[s, lo + P:hi].any()
 
 
+def _host_row_lse(oracle, case):
+    """ln sum_j exp(q_i.k_j / sqrt(D)) over the keys window row i sees: the normaliser a prefill
+    attention kernel hands over.  An INPUT of csp_score_lse, computed here in float64."""
+    G = case.H_q // case.H_kv
+    lse = np.zeros((case.B, case.H_q, case.O), dtype=np.float64)
+    for b in range(case.B):
+        lo, hi = int(case.cu_seqlens[b]), int(case.cu_seqlens[b + 1])
+        L = hi - lo
+        for h in range(case.H_q):
+            q = oracle.to_f64(case.q_win[b, h], case.dtype)
+            k = oracle.to_f64(case.k[h // G, lo:hi], case.dtype)
+            S = q @ k.T / np.sqrt(case.D)
+            S[np.arange(L)[None, :] > (L - case.O + np.arange(case.O))[:, None]] = -np.inf
+            m = S.max(axis=1)
+            lse[b, h] = m + np.log(np.exp(S - m[:, None]).sum(axis=1))
+    return lse
+
+
+@pytest.mark.parametrize("name", ["bf16_d128_o64", "f32_d64_o32_tiny_shape", "o100_r17", "nscore_1", "nscore_2p5_f32",
+                                  "gqa_group4", "ragged_batch", "mixed_window", "long_multi_chunk"])
+def test_score_with_supplied_row_lse(gpu, oracle, name):
+    """csp_score_lse: the window rows' log-sum-exp comes from the caller, the keys are read once; the
+    scores must match the oracle (which normalises by itself) and csp_score."""
+    U = _util()
+    case = _score_case(name, **SCORE_CASES[name])
+    _say(f"[score_lse] case={name}")
+    dc = U.DeviceCase(case)
+    lse = torch.from_numpy(_host_row_lse(oracle, case).astype(np.float32)).to(gpu)
+    dc.layer.score(dc.q_win, dc.k, dc.modality)
+    ref_self, ref_cross = dc.layer.score_self.clone(), dc.layer.score_cross.clone()
+    dc.layer.score_self.fill_(-1.0); dc.layer.score_cross.fill_(-1.0)
+    dc.layer.ws_score.zero_()          # no statistics left over from csp_score
+    dc.layer.score_lse(dc.q_win, dc.k, dc.modality, lse)
+    torch.cuda.synchronize()
+    g_self, g_cross = dc.layer.score_self.cpu().numpy(), dc.layer.score_cross.cpu().numpy()
+    for b in range(case.B):
+        lo, hi = int(case.cu_seqlens[b]), int(case.cu_seqlens[b + 1])
+        P = hi - lo - case.R
+        for s in range(case.H_q // case.sel_group):
+            a_s, a_c = oracle.group_scores(case, b, s)
+            U.assert_scores_close(g_self[s, lo:lo + P], a_s[:P], f"{name} b{b} s{s} self")
+            U.assert_scores_close(g_cross[s, lo:lo + P], a_c[:P], f"{name} b{b} s{s} cross")
+            assert not g_self[s, lo + P:hi].any() and not g_cross[s, lo + P:hi].any()
+    # against csp_score: the same weights up to the rounding of the normaliser
+    np.testing.assert_allclose(g_self, ref_self.cpu().numpy(), rtol=1e-4, atol=1e-7)
+    np.testing.assert_allclose(g_cross, ref_cross.cpu().numpy(), rtol=1e-4, atol=1e-7)
+
+
 def test_score_noncausal(gpu, oracle):
     U = _util()
     case = _score_case("noncausal", O=32, R=32)
