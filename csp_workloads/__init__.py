@@ -199,7 +199,7 @@ def make_case(name: str, *, dtype: str, H_q: int, H_kv: int, D: int, O: int, R: 
                 spans=[list(s) for s in layouts])
 
 
-# --- the BASELINE configurations -------------------------------------------
+# --- the benchmark configurations ----------------------------------------------
 def case_tiny(seed: int = 0) -> Case:
     """Tiny CPU-checkable case: B=1, 8 heads (MHA), D=64, fp32, L=512, O=R=32,
     T=256."""
