@@ -23,7 +23,10 @@ namespace {
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = 4;
-constexpr int kDecUnroll = 4;
+#ifndef CSP_DECODE_UNROLL
+#define CSP_DECODE_UNROLL 4
+#endif
+constexpr int kDecUnroll = CSP_DECODE_UNROLL;
 
 template <typename E> struct Unpack;
 template <> struct Unpack<bf16_tag> {
@@ -243,9 +246,12 @@ hipError_t launch_g(const DecodeParams& p, hipStream_t s) {
 
 }  // namespace
 
+#ifndef CSP_DECODE_TARGET_WGS
+#define CSP_DECODE_TARGET_WGS 512
+#endif
 int decode_num_splits(int B, int H_kv, int max_kv_len) {
     const int64_t heads = (int64_t)B * H_kv;
-    int n = (int)((1024 + heads - 1) / heads);
+    int n = (int)((CSP_DECODE_TARGET_WGS + heads - 1) / heads);
     const int by_len = max_kv_len / 256;
     if (n > by_len) n = by_len;
     if (n > 64) n = 64;

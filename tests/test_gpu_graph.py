@@ -68,4 +68,6 @@ def test_decode_step_graph_replays_match_eager(gpu, oracle):
         torch.cuda.synchronize()                     # eager work and a sync between replays
         assert torch.equal(lay.out, eager[t]), f"replay {t} differs from the eager step"
         assert torch.equal(lay.kv_len, len0 + t + 1)
-    assert torch.equal(lay.k_cache, k1) and torch.equal(lay.v_cache, v1)
+    # bit patterns: rows past the live length are uninitialised memory and may hold NaNs
+    assert torch.equal(lay.k_cache.view(torch.int16), k1.view(torch.int16))
+    assert torch.equal(lay.v_cache.view(torch.int16), v1.view(torch.int16))
