@@ -206,26 +206,44 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(DecodeParams p) {
     const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
     const float* part = p.part + ((size_t)(b * p.H_q + hq) * p.n_splits) * PSTRIDE;
     const float NEG_INF = -__builtin_inff();
-    float M = NEG_INF;
-    for (int s = 0; s < p.n_splits; ++s) M = fmaxf(M, part[s * PSTRIDE + D]);
+    // everything this thread needs is requested up front (one memory round trip per four splits)
+    const bool bump = p.k_new != nullptr && d == 0 && hq % p.G == 0;
+    const int hk = hq / p.G;
+    const int len = bump ? p.kv_len[b * p.H_kv + hk] : 0;
+    float M = NEG_INF, od = 0.f, ls = 0.f;
+    for (int s0 = 0; s0 < p.n_splits; s0 += 4) {
+        float m[4], l[4], o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool valid = s0 + u < p.n_splits;
+            const float* ps = part + (size_t)(valid ? s0 + u : s0) * PSTRIDE;
+            m[u] = ps[D];
+            l[u] = ps[D + 1];
+            o[u] = ps[d];
+            if (!valid) m[u] = NEG_INF;
+        }
+        const float Mn = fmaxf(fmaxf(fmaxf(m[0], m[1]), fmaxf(m[2], m[3])), M);
+        if (Mn == NEG_INF) continue;      // empty splits only so far
+        const float keep = fast_exp2(M - Mn);  // 0 while M is still -inf
+        od *= keep;
+        ls *= keep;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float sc = fast_exp2(m[u] - Mn);  // 0 for an empty or missing split
+            od = fmaf(o[u], sc, od);
+            ls = fmaf(l[u], sc, ls);
+        }
+        M = Mn;
+    }
     float outv = 0.f;
     if (M != NEG_INF) {
-        float od = 0.f, ls = 0.f;
-        for (int s = 0; s < p.n_splits; ++s) {
-            const float sc = fast_exp2(part[s * PSTRIDE + D] - M);
-            od += part[s * PSTRIDE + d] * sc;
-            ls += part[s * PSTRIDE + D + 1] * sc;
-        }
         // n + sum_u e^{s_u}, both scaled by e^{-max}: n enters once, here
         ls += p.n_decode * fast_exp2(-M);
         outv = od / ls;
     }
     p.out[(size_t)(b * p.H_q + hq) * D + d] = outv;
-    if (p.k_new != nullptr && d == 0 && hq % p.G == 0) {  // the fused append becomes visible to the next call
-        const int hk = hq / p.G;
-        const int len = p.kv_len[b * p.H_kv + hk];
-        if (len >= 0 && len < p.cache_cap && len < p.max_kv_len) p.kv_len[b * p.H_kv + hk] = len + 1;
-    }
+    // the fused append becomes visible to the next call
+    if (bump && len >= 0 && len < p.cache_cap && len < p.max_kv_len) p.kv_len[b * p.H_kv + hk] = len + 1;
 }
 
 template <typename E, int D, int GT>
