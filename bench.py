@@ -351,7 +351,7 @@ def cpu_baseline(cfg, inputs, budget_frac, target_s):
 
     # batches of 4 problems per thread (different heads each time) until the time target is met
     per_batch, n, t1, start = 4 * threads, 0, 0.0, 0
-    while t1 < target_s and n < 64 * threads:
+    while t1 < target_s and n < 256 * threads:
         q, k, v, m = fetch_range(start, per_batch)
         t1 += run(q, k, v, m)
         n += per_batch
