@@ -28,8 +28,11 @@
 namespace csp {
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
+#ifndef CSP_SCORE_WAVES
+#define CSP_SCORE_WAVES 4
+#endif
+constexpr int kWaves = CSP_SCORE_WAVES;
+constexpr int kThreads = 64 * kWaves;
 constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
 
 // Prefetch depth (tiles in flight per wavefront) of the two passes for 2-byte elements.
@@ -123,7 +126,8 @@ template <int D, int NQB>
 struct QFrags<bf16_tag, D, NQB, true> {
     static constexpr int NK = D / 16;
     __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* q_lds) {
-        constexpr int IT = NQB * NK * 64 / kThreads;  // 16-byte pieces per thread
+        constexpr int N = NQB * NK * 64;                      // 16-byte pieces in all
+        constexpr int IT = (N + kThreads - 1) / kThreads;     // ... per thread
         u32x4 w[IT];
 #pragma unroll
         for (int k = 0; k < IT; ++k) {                // all loads first, then all LDS writes
@@ -131,10 +135,11 @@ struct QFrags<bf16_tag, D, NQB, true> {
             const int l = e & 63, s = (e >> 6) % NK, nb = e / (64 * NK);
             const int row = nb * 32 + (l & 31);
             w[k] = u32x4{0u, 0u, 0u, 0u};
-            if (row < O) w[k] = *reinterpret_cast<const u32x4*>(qhead + ((size_t)row * D + s * 16 + (l >> 5) * 8) * 2);
+            if (e < N && row < O) w[k] = *reinterpret_cast<const u32x4*>(qhead + ((size_t)row * D + s * 16 + (l >> 5) * 8) * 2);
         }
 #pragma unroll
-        for (int k = 0; k < IT; ++k) reinterpret_cast<u32x4*>(q_lds)[tid + k * kThreads] = w[k];
+        for (int k = 0; k < IT; ++k)
+            if (tid + k * kThreads < N) reinterpret_cast<u32x4*>(q_lds)[tid + k * kThreads] = w[k];
     }
     __device__ __forceinline__ bf16x8 get(int nb, int s, int lane, const float* q_lds) const {
         return reinterpret_cast<const bf16x8*>(q_lds)[(nb * NK + s) * 64 + lane];
@@ -649,7 +654,10 @@ hipError_t launch_nqb(const ScoreParams& p, hipStream_t s) {
 int score_chunk_keys(int B, int H_q, int max_seqlen) {
     // largest chunk that still gives every compute unit two workgroups (one resident set, no
     // second round with a ragged tail): long chunks amortise the per-head set-up of a workgroup
-    int ck = 4096;
+#ifndef CSP_SCORE_MAX_CHUNK
+#define CSP_SCORE_MAX_CHUNK 4096
+#endif
+    int ck = CSP_SCORE_MAX_CHUNK;
     while (ck > 128 && (int64_t)B * H_q * ((max_seqlen + ck - 1) / ck) < CSP_SCORE_MIN_TASKS) ck >>= 1;
     return ck;
 }
