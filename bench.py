@@ -215,13 +215,14 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
     if streams is not None:
         # per-call figures of the pruning kernels: one extra, untimed pass on a single stream
         probe = Timer()
-        run_pass(cfg, inputs, layers, dec, 0, probe, sample_every=4)
+        run_pass(cfg, inputs, layers, dec, 0, probe, sample_every=1)
         torch.cuda.synchronize()
         ms.update({k: v for k, v in probe.totals_ms().items() if k in ("score", "select", "compact")})
     n_layers, B, H, D, L, O = len(layers), cfg["B"], cfg["H"], cfg["D"], cfg["L"], cfg["O"]
     e = 2
     Hs = H // sel_group                           # index sets per sequence
     avg = lambda xs: sum(xs) / max(len(xs), 1)
+    med = lambda xs: sorted(xs)[len(xs) // 2] if xs else 0.0
     # algorithmic bytes per launch (one layer)
     by_score = B * (H * L * D * e + H * O * D * e + L + 2 * Hs * (L - O) * 4)
     by_select = B * (2 * Hs * (L - O) * 4 + Hs * T * 4)
@@ -236,9 +237,12 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
         prune_gbps=n_layers * (by_score + by_select + by_compact) / (prune_ms * 1e-3) / 1e9,
         ms_per_step=wall / steps * 1e3,
         kernels={
-            "score(2 kernels)": dict(ms=avg(ms["score"]), gbps=by_score / (avg(ms["score"]) * 1e-3) / 1e9, bytes=by_score),
-            "select": dict(ms=avg(ms["select"]), gbps=by_select / (avg(ms["select"]) * 1e-3) / 1e9, bytes=by_select),
-            "compact": dict(ms=avg(ms["compact"]), gbps=by_compact / (avg(ms["compact"]) * 1e-3) / 1e9, bytes=by_compact),
+            "score(2 kernels)": dict(ms=avg(ms["score"]), ms_median=med(ms["score"]), samples=len(ms["score"]),
+                                     gbps=by_score / (avg(ms["score"]) * 1e-3) / 1e9, bytes=by_score),
+            "select": dict(ms=avg(ms["select"]), ms_median=med(ms["select"]), samples=len(ms["select"]),
+                           gbps=by_select / (avg(ms["select"]) * 1e-3) / 1e9, bytes=by_select),
+            "compact": dict(ms=avg(ms["compact"]), ms_median=med(ms["compact"]), samples=len(ms["compact"]),
+                            gbps=by_compact / (avg(ms["compact"]) * 1e-3) / 1e9, bytes=by_compact),
         })
     # kept keys per (sequence, index set): below T when the two top-K sets overlap (mixed windows)
     res["kept_mean"] = float(torch.stack([l.kept_cnt[:, :, 0].float().mean() for l in layers]).mean())
@@ -249,7 +253,8 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
                    decode_gbps=by_decode * n_layers * decode_steps / (dec_ms * 1e-3) / 1e9)
         # the whole step: algorithmic bytes of both phases over the sum of their event times
         res["step_gbps"] = n_layers * (by_score + by_select + by_compact + by_decode * decode_steps) / ((prune_ms + dec_ms) * 1e-3) / 1e9
-        res["kernels"]["decode_split"] = dict(ms=call_ms, gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
+        res["kernels"]["decode_split"] = dict(ms=call_ms, ms_median=med(ms["decode_split"]), samples=len(ms["decode_split"]),
+                                              gbps=by_decode / (call_ms * 1e-3) / 1e9, bytes=by_decode)
     del layers
     torch.cuda.empty_cache()
     return res
@@ -357,7 +362,22 @@ def cpu_baseline(cfg, inputs, budget_frac, target_s):
         n += per_batch
         start += per_batch
     seq_layers = n / H                             # one (layer, sequence) needs all H heads
-    return dict(value=seq_layers * L / t1, unit="tokens/s", cores=threads, kind="oracle",
+    # the same code on one thread, on two problems
+    orc.set_threads(1)
+    q, k, v, m = fetch_range(0, 2)
+    t_one = run(q, k, v, m)
+    orc.set_threads(threads)
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return dict(value=seq_layers * L / t1, unit="tokens/s", cores=threads, kind="oracle", cpu_model=model,
+                one_thread_value=(2 / H) * L / t_one,
                 sample=f"{n} (sequence, head) problems of layer 0 at L={L}: score+select+gather and one decode step each, "
                        f"{t1:.1f} s of wall time on {threads} OpenMP threads, scaled linearly (heads are independent)")
 
@@ -446,6 +466,9 @@ def main():
         "step_hbm_gbps": main_res.get("step_gbps"),
         "step_frac_of_peak": (main_res.get("step_gbps") or 0.0) / HBM_PEAK_GBPS,
         "copy_peak_gbps": peak_copy,
+        "prune_frac_of_copy_peak": main_res["prune_gbps"] / peak_copy,
+        "decode_frac_of_copy_peak": (main_res.get("decode_gbps") or 0.0) / peak_copy,
+        "head_tokens_per_s": main_res["tokens_per_s"] * cfg["H"],
         "kernels": kern,
         "roofline": roof,
         "cpu_baseline": cpu,
