@@ -255,6 +255,16 @@ __device__ __forceinline__ void stats_tile(f32x16 (&acc)[NQB], float c, int j0, 
     }
 }
 
+// Workgroup -> task, XCD-aware.  Workgroups go to the 8 XCDs round-robin by their linear id, and
+// each XCD has its own L2.  Tasks are numbered so that the `share` tasks that stream the same
+// keys (the query heads of a GQA group, the head slices of a selection group) are consecutive;
+// this puts each such run on one XCD, back to back, so the keys come from HBM once and from that
+// XCD's L2 afterwards.  With share == 1 the mapping is the identity.
+__device__ __forceinline__ int xcd_task(int wg, int share) {
+    const int xcd = wg & 7, j = wg >> 3;
+    return ((j / share) * 8 + xcd) * share + j % share;
+}
+
 // ---------------------------------------------------------------------------
 // Pass A: per (sequence, query head, chunk) partial row statistics.
 // ---------------------------------------------------------------------------
@@ -264,9 +274,14 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     using QF = QFrags<E, D, NQB, kQaLds>;
     using SM = Smem<E, D, NQB, kQaLds>;
     extern __shared__ __align__(16) char smem[];
-    const int chunk = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+    // task = (query head within its GQA group, chunk, KV head, sequence), the first index fastest
+    int task = xcd_task(blockIdx.x, p.G);
+    if (task >= p.G * p.n_chunks * p.view.H_kv * p.B) return;
+    const int g_in = task % p.G; task /= p.G;
+    const int chunk = task % p.n_chunks; task /= p.n_chunks;
+    const int hk = task % p.view.H_kv, b = task / p.view.H_kv;
+    const int hq = hk * p.G + g_in;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    const int hk = hq / p.G;
     const int L = view_len(p.view, b, hk);
     const int c0 = chunk * p.chunk_keys;
     if (c0 >= L || view_fits(p.view, b, L)) return;
@@ -420,9 +435,15 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     using QF = QFrags<E, D, NQB, kQbLds>;
     using SM = Smem<E, D, NQB, kQbLds>;
     extern __shared__ __align__(16) char smem[];
-    // blockIdx.y = (selection group, slice of its heads); a group summed by one workgroup
-    // (gsplit == 1) writes the result, otherwise each slice writes its own partial array
-    const int chunk = blockIdx.x, sg = blockIdx.y / p.gsplit, slice = blockIdx.y % p.gsplit, b = blockIdx.z;
+    // a group summed by one workgroup (gsplit == 1) writes the result, otherwise each slice of
+    // its heads writes its own partial array
+    // task = (head slice, chunk, selection group, sequence), the first index fastest
+    int task = xcd_task(blockIdx.x, p.gsplit);
+    const int H_sel = p.H_q / p.sel_group;
+    if (task >= p.gsplit * p.n_chunks * H_sel * p.B) return;
+    const int slice = task % p.gsplit; task /= p.gsplit;
+    const int chunk = task % p.n_chunks; task /= p.n_chunks;
+    const int sg = task % H_sel, b = task / H_sel;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int L = view_len(p.view, b, (sg * p.sel_group) / p.G);
     const int c0 = chunk * p.chunk_keys;
@@ -623,8 +644,9 @@ hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
         if (e != hipSuccess) return e;
     }
     const dim3 block(kThreads);
-    const dim3 grid_a(p.n_chunks, p.H_q, p.B);
-    const dim3 grid_b(p.n_chunks, (p.H_q / p.sel_group) * p.gsplit, p.B);
+    auto padded = [](int64_t tasks, int share) { return (unsigned)((tasks + 8 * share - 1) / (8 * share) * (8 * share)); };
+    const dim3 grid_a(padded((int64_t)p.n_chunks * p.H_q * p.B, p.G));
+    const dim3 grid_b(padded((int64_t)p.n_chunks * (p.H_q / p.sel_group) * p.gsplit * p.B, p.gsplit));
     hipError_t e = hipSuccess;
     if (p.row_lse == nullptr) {  // the row normalisers are not given: first pass over the keys
         hipLaunchKernelGGL(ka, grid_a, block, smem_a, s, p);
