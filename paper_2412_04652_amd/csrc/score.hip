@@ -178,16 +178,26 @@ __device__ __forceinline__ auto k_frag(const char* tile, int s, int lane) {
 
 // Global -> registers: tile rows j0 .. j0+31 of one (sequence, KV head); rows
 // past the end of the sequence re-read row L-1 (masked by the caller).
-template <typename E, int D>
+template <typename E, int D, bool REUSED>
 __device__ __forceinline__ void load_tile(u32x4 (&st)[(Geom<E, D>::NLD)], const char* kbase, int64_t tok_bytes,
                                           int j0, int L, int lane) {
     using G = Geom<E, D>;
+    if constexpr (!REUSED) {
 #pragma unroll
-    for (int i = 0; i < G::NLD; ++i) {
-        int j = j0 + i * G::RPI + lane / G::CPR;
-        j = j < L ? j : L - 1;
-        // streamed once per pass: non-temporal, measurably faster than plain loads here
-        st[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase + (int64_t)j * tok_bytes + (lane % G::CPR) * 16));
+        for (int i = 0; i < G::NLD; ++i) {
+            int j = j0 + i * G::RPI + lane / G::CPR;
+            j = j < L ? j : L - 1;
+            // streamed once per pass: non-temporal, measurably faster than plain loads here
+            st[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kbase + (int64_t)j * tok_bytes + (lane % G::CPR) * 16));
+        }
+    } else {
+        // other workgroups on this XCD stream the same keys at the same time: keep them in L2
+#pragma unroll
+        for (int i = 0; i < G::NLD; ++i) {
+            int j = j0 + i * G::RPI + lane / G::CPR;
+            j = j < L ? j : L - 1;
+            st[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)j * tok_bytes + (lane % G::CPR) * 16);
+        }
     }
 }
 
@@ -268,7 +278,9 @@ __device__ __forceinline__ int xcd_task(int wg, int share) {
 // ---------------------------------------------------------------------------
 // Pass A: per (sequence, query head, chunk) partial row statistics.
 // ---------------------------------------------------------------------------
-template <typename E, int D, int NQB>
+// REUSED: other workgroups stream the same keys (GQA): plain loads that stay in L2 instead of
+// non-temporal ones.
+template <typename E, int D, int NQB, bool REUSED>
 __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void score_stats_kernel(ScoreParams p) {
     using G = Geom<E, D>;
     using QF = QFrags<E, D, NQB, kQaLds>;
@@ -319,7 +331,9 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     // Tiles are visited in a rotated order (tile (t + rot) mod ntiles at step t) with a
     // different rotation per wavefront and workgroup: all key runs are aligned to large powers
     // of two, and wavefronts walking them in lockstep would hit the same memory channels.
-    const int rot = ntiles > 0 ? (int)((chunk * 5u + hq * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    // (the query heads of a GQA group share the rotation: they start together on one XCD and
+    // walk the same keys in the same order, so all but the first find a tile in that XCD's L2)
+    const int rot = ntiles > 0 ? (int)((chunk * 5u + hk * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
@@ -327,7 +341,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     // the key stream starts first; the queries (L2-resident, small) follow
     if (ntiles > 0) {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
+        for (int u = 0; u < PF; ++u) load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
     }
     QF qf;
     qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
@@ -344,7 +358,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
                 store_tile<E, D>(st[u], tile, lane);
                 wave_lds_sync();
             }
-            load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
+            load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
             if (!live) continue;
 
             f32x16 acc[NQB];
@@ -429,7 +443,7 @@ __device__ __forceinline__ void colsum_tile(const f32x16 (&acc)[NQB], float c, c
 // ---------------------------------------------------------------------------
 // Pass B: per (sequence, selection group, chunk) column sums.
 // ---------------------------------------------------------------------------
-template <typename E, int D, int NQB>
+template <typename E, int D, int NQB, bool REUSED>
 __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void score_colsum_kernel(ScoreParams p) {
     using G = Geom<E, D>;
     using QF = QFrags<E, D, NQB, kQbLds>;
@@ -514,7 +528,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
         if (ntiles > 0) {
 #pragma unroll
             for (int u = 0; u < PF; ++u) {
-                load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
+                load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
                 kmod[u] = load_mod(tile_key(u));
             }
         }
@@ -565,7 +579,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
                 }
                 const bool key_text = kmod[u] == 0;
                 // one tile of loads per iteration on every path (see the ring in pass A)
-                load_tile<E, D>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
+                load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
                 kmod[u] = load_mod(tile_key(t + PF));
                 if (!live) continue;
 
@@ -633,8 +647,9 @@ __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
 template <typename E, int D, int NQB>
 hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
     const size_t smem_a = Smem<E, D, NQB, kQaLds>::total, smem_b = Smem<E, D, NQB, kQbLds>::total;
-    auto ka = score_stats_kernel<E, D, NQB>;
-    auto kb = score_colsum_kernel<E, D, NQB>;
+    // keys that several workgroups (GQA) or several head iterations of one workgroup stream stay in L2
+    auto ka = p.G > 1 ? score_stats_kernel<E, D, NQB, true> : score_stats_kernel<E, D, NQB, false>;
+    auto kb = (p.G > 1 || p.gper > 1) ? score_colsum_kernel<E, D, NQB, true> : score_colsum_kernel<E, D, NQB, false>;
     if (smem_a > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(ka), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_a);
         if (e != hipSuccess) return e;
