@@ -265,6 +265,34 @@ __device__ __forceinline__ void stats_tile(f32x16 (&acc)[NQB], float c, int j0, 
     }
 }
 
+#ifndef CSP_SCORE_INTERLEAVE
+#define CSP_SCORE_INTERLEAVE 0
+#endif
+// The 32-key tiles one wavefront of workgroup `chunk` visits: first key base + step*stride.
+// Contiguous: the workgroup owns keys [chunk*chunk_keys, (chunk+1)*chunk_keys) and its wavefronts
+// take the tiles round-robin.  Interleaved: the n_chunks workgroups of a (sequence, head) take
+// groups of kWaves consecutive tiles round-robin, so they sweep the head's keys side by side.
+struct TileWalk {
+    int ntiles, base, stride;
+};
+__device__ __forceinline__ TileWalk tile_walk(int L, int chunk, int chunk_keys, int n_chunks, int wave) {
+    TileWalk w;
+    if (CSP_SCORE_INTERLEAVE) {
+        const int nt_seq = (L + kTile - 1) / kTile;
+        const int first = chunk * kWaves + wave, step = n_chunks * kWaves;
+        w.ntiles = nt_seq > first ? (nt_seq - first + step - 1) / step : 0;
+        w.base = first * kTile;
+        w.stride = step * kTile;
+    } else {
+        const int c0 = chunk * chunk_keys;
+        const int ntc = c0 < L ? (min(c0 + chunk_keys, L) - c0 + kTile - 1) / kTile : 0;
+        w.ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
+        w.base = c0 + wave * kTile;
+        w.stride = kWaves * kTile;
+    }
+    return w;
+}
+
 // Workgroup -> task, XCD-aware.  Workgroups go to the 8 XCDs round-robin by their linear id, and
 // each XCD has its own L2.  Tasks are numbered so that the `share` tasks that stream the same
 // keys (the query heads of a GQA group, the head slices of a selection group) are consecutive;
@@ -295,8 +323,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     const int hq = hk * p.G + g_in;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int L = view_len(p.view, b, hk);
-    const int c0 = chunk * p.chunk_keys;
-    if (c0 >= L || view_fits(p.view, b, L)) return;
+    if ((!CSP_SCORE_INTERLEAVE && chunk * p.chunk_keys >= L) || view_fits(p.view, b, L)) return;
     const int O = p.O;
     const float c = p.scale_log2;
     const float NEG_INF = -__builtin_inff();
@@ -310,8 +337,8 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
 
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
     // so a workgroup sweeps its chunk as one stream
-    const int ntc = (min(c0 + p.chunk_keys, L) - c0 + kTile - 1) / kTile;
-    const int ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
+    const TileWalk walk = tile_walk(L, chunk, p.chunk_keys, p.n_chunks, wave);
+    const int ntiles = walk.ntiles;
 
     float m_run[NQB], l_run[NQB];
     int pos_q[NQB];  // absolute position of this lane's query in block nb
@@ -333,10 +360,10 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     // of two, and wavefronts walking them in lockstep would hit the same memory channels.
     // (the query heads of a GQA group share the rotation: they start together on one XCD and
     // walk the same keys in the same order, so all but the first find a tile in that XCD's L2)
-    const int rot = ntiles > 0 ? (int)((chunk * 5u + hk * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    const int rot = ntiles > 0 ? (int)(((CSP_SCORE_INTERLEAVE ? 0u : chunk * 5u) + hk * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
-        return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
+        return t < ntiles ? walk.base + (tt < ntiles ? tt : tt - ntiles) * walk.stride : L - 1;
     };
     // the key stream starts first; the queries (L2-resident, small) follow
     if (ntiles > 0) {
@@ -460,8 +487,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     const int sg = task % H_sel, b = task / H_sel;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int L = view_len(p.view, b, (sg * p.sel_group) / p.G);
-    const int c0 = chunk * p.chunk_keys;
-    if (c0 >= L || view_fits(p.view, b, L)) return;
+    if ((!CSP_SCORE_INTERLEAVE && chunk * p.chunk_keys >= L) || view_fits(p.view, b, L)) return;
     const int O = p.O, R = p.R;
     const float c = p.scale_log2;
     const uint8_t* const mod = p.modality + view_mod0(p.view, b, sg);
@@ -472,7 +498,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     float* const out_self = p.gsplit > 1 ? p.slice_self + slice_off : p.score_self;
     float* const out_cross = p.gsplit > 1 ? p.slice_cross + slice_off : p.score_cross;
     const float NEG_INF = -__builtin_inff();
-    const int n_chunks_b = (L + p.chunk_keys - 1) / p.chunk_keys;
+    const int n_chunks_b = CSP_SCORE_INTERLEAVE ? p.n_chunks : (L + p.chunk_keys - 1) / p.chunk_keys;  // chunks that wrote statistics
 
     char* tile = smem + wave * G::TILE_LDS;
     float* nlse_s = reinterpret_cast<float*>(smem + SM::off_nlse);
@@ -500,18 +526,18 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
 
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
     // so a workgroup sweeps its chunk as one stream
-    const int ntc = (min(c0 + p.chunk_keys, L) - c0 + kTile - 1) / kTile;
-    const int ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
+    const TileWalk walk = tile_walk(L, chunk, p.chunk_keys, p.n_chunks, wave);
+    const int ntiles = walk.ntiles;
     const int rank_end = L - R;                                   // keys >= rank_end are not ranked
     const int mask_from = min(rank_end, p.causal ? L - O : L);    // below: no masking needed
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
     constexpr int PF = Prefetch<E>::B;
     // same rotated visiting order as pass A (the two passes need not agree)
-    const int rot = ntiles > 0 ? (int)((chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    const int rot = ntiles > 0 ? (int)(((CSP_SCORE_INTERLEAVE ? 0u : chunk * 5u) + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
-        return t < ntiles ? c0 + ((tt < ntiles ? tt : tt - ntiles) * kWaves + wave) * kTile : L - 1;
+        return t < ntiles ? walk.base + (tt < ntiles ? tt : tt - ntiles) * walk.stride : L - 1;
     };
     auto load_mod = [&](int j0) -> uint8_t {  // modality of key j0 + lane%32, fetched with its tile
         const int j = j0 + (lane & 31);
