@@ -92,7 +92,7 @@ const char* csp_version(void) { return "csp-gfx950 0.1"; }
 size_t csp_score_workspace_bytes(const csp_desc* d) {
     Checked c;
     if (!d || d->B <= 0 || d->H_q <= 0 || d->max_seqlen <= 0 || d->window_O <= 0) return 0;
-    const int ck = score_chunk_keys(d->B, d->H_q, d->max_seqlen);
+    const int ck = score_chunk_keys(d->B, d->H_q, d->max_seqlen, d->dtype, d->D, d->window_O);
     const size_t n_chunks = (size_t)(d->max_seqlen + ck - 1) / ck;
     (void)c;
     size_t bytes = (size_t)d->B * d->H_q * n_chunks * d->window_O * 2 * sizeof(float);
@@ -128,7 +128,7 @@ static int score_common(const csp_desc* d, const void* q_win, const void* k, con
     p.score_elems = (int64_t)c.H_sel * c.total_tokens;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
-    p.chunk_keys = score_chunk_keys(d->B, d->H_q, d->max_seqlen);
+    p.chunk_keys = score_chunk_keys(d->B, d->H_q, d->max_seqlen, d->dtype, d->D, d->window_O);
     p.n_chunks = (d->max_seqlen + p.chunk_keys - 1) / p.chunk_keys;
     p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
     p.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, p.n_chunks);
@@ -323,7 +323,7 @@ struct RepruneLayout {
 };
 RepruneLayout reprune_layout(const csp_desc* d, int H_sel, int row_bytes, int cache_cap) {
     RepruneLayout l;
-    l.chunk_keys = score_chunk_keys(d->B, d->H_q, cache_cap);
+    l.chunk_keys = score_chunk_keys(d->B, d->H_q, cache_cap, d->dtype, d->D, d->window_O);
     l.n_chunks = (cache_cap + l.chunk_keys - 1) / l.chunk_keys;
     l.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, l.n_chunks);
     l.gsplit = (d->sel_group + l.gper - 1) / l.gper;

@@ -185,7 +185,7 @@ hipError_t launch_window_push(const WindowParams& p, hipStream_t s);
 hipError_t launch_window_unroll(const WindowParams& p, hipStream_t s);
 
 // host-side sizing rules shared by the *_workspace_bytes functions and the launchers
-int score_chunk_keys(int B, int H_q, int max_seqlen);
+int score_chunk_keys(int B, int H_q, int max_seqlen, int dtype, int D, int O);
 // heads of a selection group that one workgroup of the column-sum pass sums itself
 int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks);
 int decode_num_splits(int B, int H_kv, int max_kv_len);

@@ -265,31 +265,19 @@ __device__ __forceinline__ void stats_tile(f32x16 (&acc)[NQB], float c, int j0, 
     }
 }
 
-#ifndef CSP_SCORE_INTERLEAVE
-#define CSP_SCORE_INTERLEAVE 0
-#endif
-// The 32-key tiles one wavefront of workgroup `chunk` visits: first key base + step*stride.
-// Contiguous: the workgroup owns keys [chunk*chunk_keys, (chunk+1)*chunk_keys) and its wavefronts
-// take the tiles round-robin.  Interleaved: the n_chunks workgroups of a (sequence, head) take
-// groups of kWaves consecutive tiles round-robin, so they sweep the head's keys side by side.
+// The 32-key tiles one wavefront of workgroup `chunk` visits: the workgroup owns keys
+// [chunk*chunk_keys, (chunk+1)*chunk_keys) and its wavefronts take the tiles round-robin;
+// first key of a wavefront's step: base + step*stride.
 struct TileWalk {
     int ntiles, base, stride;
 };
-__device__ __forceinline__ TileWalk tile_walk(int L, int chunk, int chunk_keys, int n_chunks, int wave) {
+__device__ __forceinline__ TileWalk tile_walk(int L, int chunk, int chunk_keys, int wave) {
     TileWalk w;
-    if (CSP_SCORE_INTERLEAVE) {
-        const int nt_seq = (L + kTile - 1) / kTile;
-        const int first = chunk * kWaves + wave, step = n_chunks * kWaves;
-        w.ntiles = nt_seq > first ? (nt_seq - first + step - 1) / step : 0;
-        w.base = first * kTile;
-        w.stride = step * kTile;
-    } else {
-        const int c0 = chunk * chunk_keys;
-        const int ntc = c0 < L ? (min(c0 + chunk_keys, L) - c0 + kTile - 1) / kTile : 0;
-        w.ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
-        w.base = c0 + wave * kTile;
-        w.stride = kWaves * kTile;
-    }
+    const int c0 = chunk * chunk_keys;
+    const int ntc = c0 < L ? (min(c0 + chunk_keys, L) - c0 + kTile - 1) / kTile : 0;
+    w.ntiles = ntc > wave ? (ntc - wave + kWaves - 1) / kWaves : 0;
+    w.base = c0 + wave * kTile;
+    w.stride = kWaves * kTile;
     return w;
 }
 
@@ -323,7 +311,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     const int hq = hk * p.G + g_in;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int L = view_len(p.view, b, hk);
-    if ((!CSP_SCORE_INTERLEAVE && chunk * p.chunk_keys >= L) || view_fits(p.view, b, L)) return;
+    if (chunk * p.chunk_keys >= L || view_fits(p.view, b, L)) return;
     const int O = p.O;
     const float c = p.scale_log2;
     const float NEG_INF = -__builtin_inff();
@@ -337,7 +325,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
 
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
     // so a workgroup sweeps its chunk as one stream
-    const TileWalk walk = tile_walk(L, chunk, p.chunk_keys, p.n_chunks, wave);
+    const TileWalk walk = tile_walk(L, chunk, p.chunk_keys, wave);
     const int ntiles = walk.ntiles;
 
     float m_run[NQB], l_run[NQB];
@@ -360,7 +348,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     // of two, and wavefronts walking them in lockstep would hit the same memory channels.
     // (the query heads of a GQA group share the rotation: they start together on one XCD and
     // walk the same keys in the same order, so all but the first find a tile in that XCD's L2)
-    const int rot = ntiles > 0 ? (int)(((CSP_SCORE_INTERLEAVE ? 0u : chunk * 5u) + hk * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    const int rot = ntiles > 0 ? (int)((chunk * 5u + hk * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? walk.base + (tt < ntiles ? tt : tt - ntiles) * walk.stride : L - 1;
@@ -487,7 +475,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     const int sg = task % H_sel, b = task / H_sel;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int L = view_len(p.view, b, (sg * p.sel_group) / p.G);
-    if ((!CSP_SCORE_INTERLEAVE && chunk * p.chunk_keys >= L) || view_fits(p.view, b, L)) return;
+    if (chunk * p.chunk_keys >= L || view_fits(p.view, b, L)) return;
     const int O = p.O, R = p.R;
     const float c = p.scale_log2;
     const uint8_t* const mod = p.modality + view_mod0(p.view, b, sg);
@@ -498,12 +486,14 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     float* const out_self = p.gsplit > 1 ? p.slice_self + slice_off : p.score_self;
     float* const out_cross = p.gsplit > 1 ? p.slice_cross + slice_off : p.score_cross;
     const float NEG_INF = -__builtin_inff();
-    const int n_chunks_b = CSP_SCORE_INTERLEAVE ? p.n_chunks : (L + p.chunk_keys - 1) / p.chunk_keys;  // chunks that wrote statistics
+    const int n_chunks_b = (L + p.chunk_keys - 1) / p.chunk_keys;  // chunks that wrote statistics
 
     char* tile = smem + wave * G::TILE_LDS;
     float* nlse_s = reinterpret_cast<float*>(smem + SM::off_nlse);
     uint8_t* wq = reinterpret_cast<uint8_t*>(smem + SM::off_wq);
     float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
+    float* sc_lds = reinterpret_cast<float*>(smem + SM::total);  // [2][chunk_keys]: self, cross scores of the chunk
+    const int c0 = chunk * p.chunk_keys;
 
     // modality of the window rows; a window with one modality takes the fast path
     if (tid < NQB * 32) wq[tid] = tid < O ? (mod[L - O + tid] ? 1 : 0) : 2;
@@ -526,7 +516,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
 
     // the four wavefronts take the chunk's 32-key tiles round-robin (wave w: tiles w, w+4, ...),
     // so a workgroup sweeps its chunk as one stream
-    const TileWalk walk = tile_walk(L, chunk, p.chunk_keys, p.n_chunks, wave);
+    const TileWalk walk = tile_walk(L, chunk, p.chunk_keys, wave);
     const int ntiles = walk.ntiles;
     const int rank_end = L - R;                                   // keys >= rank_end are not ranked
     const int mask_from = min(rank_end, p.causal ? L - O : L);    // below: no masking needed
@@ -534,7 +524,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
 
     constexpr int PF = Prefetch<E>::B;
     // same rotated visiting order as pass A (the two passes need not agree)
-    const int rot = ntiles > 0 ? (int)(((CSP_SCORE_INTERLEAVE ? 0u : chunk * 5u) + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    const int rot = ntiles > 0 ? (int)((chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
         const int tt = t + rot;
         return t < ntiles ? walk.base + (tt < ntiles ? tt : tt - ntiles) * walk.stride : L - 1;
@@ -641,20 +631,29 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
                 ct += __shfl_xor(ct, 32);
                 if (mixed) cv += __shfl_xor(cv, 32);
                 else if (any_vis) { cv = ct; ct = 0.f; }  // an all-visual window: every row is a visual query
-                if (half == 0 && j < L) {
-                    float s_self = key_text ? ct : cv;
-                    float s_cross = key_text ? cv : ct;
-                    const size_t o = score0 + j;
-                    if (g > g_begin) {  // same thread wrote these in the previous head iteration
-                        s_self += out_self[o];
-                        s_cross += out_cross[o];
-                    }
-                    out_self[o] = s_self;
-                    out_cross[o] = s_cross;
+                // The chunk's scores are gathered in LDS and written in one burst when the workgroup
+                // is done: small stores in the loop (128 bytes per tile and array) interleave writes
+                // with the key stream and cost 15 % of the pass.  Lanes 0-31 hold the self score of
+                // key j, lanes 32-63 its cross score; the same lane owns the same key for every head
+                // of the group, so the running sum over heads is a private read-modify-write.
+                {
+                    const float s_self = key_text ? ct : cv;
+                    const float s_cross = key_text ? cv : ct;
+                    float* dst = sc_lds + (half ? p.chunk_keys : 0) + (j - c0);
+                    float val = half ? s_cross : s_self;
+                    if constexpr (REUSED) val += g > g_begin ? *dst : 0.f;
+                    *dst = val;
                 }
             }
         }
         }
+    }
+    // the chunk's scores: one coalesced burst per array
+    __syncthreads();
+    const int nk = min(p.chunk_keys, L - c0);
+    for (int i = tid; i < nk; i += kThreads) {
+        out_self[score0 + c0 + i] = sc_lds[i];
+        out_cross[score0 + c0 + i] = sc_lds[p.chunk_keys + i];
     }
 }
 
@@ -672,7 +671,7 @@ __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
 
 template <typename E, int D, int NQB>
 hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
-    const size_t smem_a = Smem<E, D, NQB, kQaLds>::total, smem_b = Smem<E, D, NQB, kQbLds>::total;
+    const size_t smem_a = Smem<E, D, NQB, kQaLds>::total, smem_b = Smem<E, D, NQB, kQbLds>::total + (size_t)2 * p.chunk_keys * sizeof(float);
     // keys that several workgroups (GQA) or several head iterations of one workgroup stream stay in L2
     auto ka = p.G > 1 ? score_stats_kernel<E, D, NQB, true> : score_stats_kernel<E, D, NQB, false>;
     auto kb = (p.G > 1 || p.gper > 1) ? score_colsum_kernel<E, D, NQB, true> : score_colsum_kernel<E, D, NQB, false>;
@@ -684,6 +683,7 @@ hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kb), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_b);
         if (e != hipSuccess) return e;
     }
+    if (smem_b > 160 * 1024) return hipErrorInvalidValue;  // excluded by score_chunk_keys
     const dim3 block(kThreads);
     auto padded = [](int64_t tasks, int share) { return (unsigned)((tasks + 8 * share - 1) / (8 * share) * (8 * share)); };
     const dim3 grid_a(padded((int64_t)p.n_chunks * p.H_q * p.B, p.G));
@@ -714,13 +714,16 @@ hipError_t launch_nqb(const ScoreParams& p, hipStream_t s) {
 #ifndef CSP_SCORE_MIN_TASKS
 #define CSP_SCORE_MIN_TASKS 512
 #endif
-int score_chunk_keys(int B, int H_q, int max_seqlen) {
+int score_chunk_keys(int B, int H_q, int max_seqlen, int dtype, int D, int O) {
     // largest chunk that still gives every compute unit two workgroups (one resident set, no
     // second round with a ragged tail): long chunks amortise the per-head set-up of a workgroup
 #ifndef CSP_SCORE_MAX_CHUNK
 #define CSP_SCORE_MAX_CHUNK 4096
 #endif
     int ck = CSP_SCORE_MAX_CHUNK;
+    // the column-sum pass keeps the chunk's scores in LDS (8 bytes per key) next to its key tiles
+    // and staged queries; fp32 with D = 128 and a window above 64 rows leaves room for 2048 keys
+    if (dtype == CSP_F32 && D == 128 && O > 64 && ck > 2048) ck = 2048;
     while (ck > 128 && (int64_t)B * H_q * ((max_seqlen + ck - 1) / ck) < CSP_SCORE_MIN_TASKS) ck >>= 1;
     return ck;
 }

@@ -10,11 +10,13 @@ import csp_workloads as W
 
 pytestmark = pytest.mark.gpu
 
-torch = pytest.importorskip("torch")
+torch = None  # imported by the `gpu` fixture: runs that select no GPU test never load it
 
 
 @pytest.fixture(scope="module")
 def gpu():
+    global torch
+    torch = pytest.importorskip("torch")
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     import paper_2412_04652_amd as P
