@@ -55,14 +55,14 @@ __global__ __launch_bounds__(kMvThreads) void reprune_move_kernel(RepruneParams 
             const int tt = t0 + u * ROWS + r;
             mv[u] = j[u] > tt && j[u] < L;  // j == tt: the row is already in place; anything else is not a valid source
             // unconditional load (row 0 when there is nothing to move) keeps the four loads in flight together
-            val[u] = *reinterpret_cast<const u32x4*>(base + (int64_t)(mv[u] ? j[u] : 0) * p.stride_tok + ch * 16);
+            val[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + (int64_t)(mv[u] ? j[u] : 0) * p.stride_tok + ch * 16));
         }
 #pragma unroll
         for (int u = 0; u < kMvUnroll; ++u) wait_for(val[u]);
         __syncthreads();
 #pragma unroll
         for (int u = 0; u < kMvUnroll; ++u)
-            if (mv[u]) *reinterpret_cast<u32x4*>(base + (int64_t)(t0 + u * ROWS + r) * p.stride_tok + ch * 16) = val[u];
+            if (mv[u]) __builtin_nontemporal_store(val[u], reinterpret_cast<u32x4*>(base + (int64_t)(t0 + u * ROWS + r) * p.stride_tok + ch * 16));
     }
 }
 
