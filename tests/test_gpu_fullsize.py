@@ -235,3 +235,35 @@ def test_gqa_large_groups_in_slices(gpu, oracle):
     cnt = lay.kept_cnt.cpu().numpy()
     for b in range(8):
         assert (cnt[b, :, 0] == budgets[b]).all()
+
+
+def test_f32_d128_window128_large_chunks(gpu, oracle):
+    """fp32 storage, head_dim 128, window 128: the shape whose column-sum pass needs the most LDS (key
+    tiles, staged fp32 queries and the chunk's scores); large enough (B=8, 32 heads, L=4096) that the
+    chunk size reaches its cap for this shape."""
+    import gpu_util as U
+    from paper_2412_04652_amd.runner import CspLayer
+    rng = np.random.default_rng(31)
+    layouts = [W.layout_random(rng, [576] * 4, 4096 - 4 * 576, 128) for _ in range(8)]
+    q, k, v, mod, cu_dev, cu = W.device_qkv(layouts, H_q=32, H_kv=32, D=128, O=128, seed=5, device=gpu)
+    qf, kf = q.float(), k.float()
+    lay = CspLayer(dtype="f32", H_q=32, H_kv=32, D=128, O=128, R=128, cu_seqlens=cu.tolist(), budgets=[2048] * 8,
+                   device=gpu)
+    print("[full] f32 d128 window 128", flush=True)
+    lay.score(qf, kf, mod)
+    lay.select(mod)
+    torch.cuda.synchronize()
+    mod_h = mod.cpu().numpy()
+    idx, cnt = lay.kept_idx.cpu().numpy(), lay.kept_cnt.cpu().numpy()
+    for b, h in [(0, 0), (5, 17), (7, 31)]:
+        lo, hi = int(cu[b]), int(cu[b + 1])
+        L = hi - lo
+        a_s, a_c = oracle.head_scores(qf[b, h].cpu().numpy().astype(np.float64), kf[h, lo:hi].cpu().numpy().astype(np.float64),
+                                      mod_h[lo:hi], 128, 0.0, True)
+        P = L - 128
+        U.assert_scores_close(lay.score_self[h, lo:lo + P].cpu().numpy(), a_s[:P], f"f32 b{b} h{h} self")
+        U.assert_scores_close(lay.score_cross[h, lo:lo + P].cpu().numpy(), a_c[:P], f"f32 b{b} h{h} cross")
+        ref_idx, rc = oracle.select(a_s, a_c, mod_h[lo:hi], 128, 128, 2048, 0.5)
+        n = int(cnt[b, h, 0])
+        assert n == rc["kept"] == 2048
+        U.assert_kept_equivalent(idx[b, h, :n], ref_idx, a_s, a_c, mod_h[lo:hi], L, 128, f"f32 b{b} h{h}")
