@@ -270,3 +270,38 @@ def test_reprune_7b_16k_layer_sampled(gpu, oracle):
         ref = oracle.decode(oracle.bf16_bits_to_f64(U.from_dev_bits(dq[b, h], "bf16")), oracle.bf16_bits_to_f64(kc[b, h, :T + 1]),
                             oracle.bf16_bits_to_f64(vc[b, h, :T + 1]), 1.0)
         U.assert_decode_close(out[b, h], ref, f"decode after reprune b{b} h{h}")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_reprune_random_shapes(gpu, oracle, seed):
+    """Randomly drawn shapes (head grouping, dtype, window and recent sizes incl. R = 0, ragged batches with
+    sequences under and over their budget, windows that still hold visual prefill queries), one to three
+    decode/re-prune cycles each."""
+    U = _util()
+    import test_gpu_random_shapes as RS
+    rng = np.random.default_rng(9000 + seed)
+    base = RS.draw_case(seed)
+    lens = np.diff(base.cu_seqlens).tolist()
+    budgets = [int(max(min(t, l), base.O, base.R, 1)) for t, l in zip(base.budget_T.tolist(), lens)]
+    cycles = [int(rng.integers(1, 12)) for _ in range(int(rng.integers(1, 4)))]
+    case = W.make_case(f"rp{seed}", dtype=base.dtype, H_q=base.H_q, H_kv=base.H_kv, D=base.D, O=base.O, R=base.R,
+                       sel_group=base.sel_group, cross_ratio=base.cross_ratio, n_score=base.n_score, layouts=base.spans,
+                       budgets=budgets, seed=seed, decode_steps=sum(cycles))
+    print(f"[reprune] random seed={seed} {case.dtype} D={case.D} H_q={case.H_q} H_kv={case.H_kv} group={case.sel_group} "
+          f"O={case.O} R={case.R} lens={lens} T={budgets} cycles={cycles}", flush=True)
+    dc = U.DeviceCase(case, decode_cap=max(cycles) + 1, reprune=True)
+    lay = dc.layer
+    lay.prune(dc.q_win, dc.k, dc.v, dc.modality)
+    sample = [(b, s) for b in range(case.B) for s in range(lay.H_sel)]
+    t = 0
+    for ci, n_steps in enumerate(cycles):
+        for _ in range(n_steps):
+            _decode_and_check(U, oracle, dc, case, t, [(0, 0)] if t % 5 == 0 else [])
+            t += 1
+        torch.cuda.synchronize()
+        before = _snapshot(U, lay, case.dtype)
+        lay.reprune()
+        torch.cuda.synchronize()
+        _check_reprune(U, oracle, lay, before, _window(case, t), dtype=case.dtype, H_q=case.H_q, H_kv=case.H_kv,
+                       sel_group=case.sel_group, O=case.O, R=case.R, budgets=budgets, n_score=case.n_score,
+                       cross_ratio=case.cross_ratio, sample=sample, what=f"random {seed} cycle {ci}")
