@@ -14,15 +14,18 @@
 //        the sum over queries of exp(S - lse) is an in-lane add chain.
 // The two orientations use the same LDS tile and the same register fragments;
 // only the operand order of the MFMA differs.
-// A workgroup is 4 wavefronts; each wavefront owns a contiguous run of keys of
-// the workgroup's chunk and streams it in tiles of 32 keys: coalesced 16-byte
+// A workgroup is 4 wavefronts that take the 32-key tiles of the workgroup's
+// chunk round-robin, in a rotated order; a tile is streamed with coalesced 16-byte
 // global loads (4 full 256-byte rows per instruction for bf16/D=128) into a
 // ring of register tiles PF tiles ahead (the loop is bound by HBM latency: the
 // bytes in flight per compute unit, not the arithmetic, set the rate), a
 // wave-private padded LDS tile as the transpose
 // between the load layout and the MFMA operand layout, no workgroup barrier
 // in the loop.  All exponentials are base 2 with log2(e)/sqrt(D) folded into
-// one FMA per element.
+// one FMA per element.  Every memory operation in the two loops is issued on
+// every path (no load or store under a branch): otherwise the compiler's wait
+// counts degrade to "wait for everything" and the prefetch is lost.  Pass B
+// keeps the chunk's scores in LDS and writes them in one burst at the end.
 #include "csp_internal.h"
 
 namespace csp {
