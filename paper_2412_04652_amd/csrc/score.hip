@@ -52,12 +52,12 @@ constexpr int kTile = 32;  // keys per wavefront tile (one MFMA block edge)
 #endif
 constexpr bool kQbLds = CSP_SCORE_QB_LDS != 0;
 #ifndef CSP_SCORE_QA_LDS
-#define CSP_SCORE_QA_LDS 1
+#define CSP_SCORE_QA_LDS 0
 #endif
 constexpr bool kQaLds = CSP_SCORE_QA_LDS != 0;
 // wavefronts per SIMD the two passes are compiled for (register budget = 512 / this)
 #ifndef CSP_SCORE_WPE_A
-#define CSP_SCORE_WPE_A 3
+#define CSP_SCORE_WPE_A 2
 #endif
 #ifndef CSP_SCORE_WPE_B
 #define CSP_SCORE_WPE_B 2
