@@ -102,7 +102,7 @@ def test_7b_16k_layer_sampled(gpu, oracle, budget):
     T = int(16384 * budget)
     print(f"[full] 7b_16k budget={budget} T={T}", flush=True)
     lay, q, k, v, mod, cu, dec = _run(gpu, layouts, H_q=32, H_kv=32, D=128, O=64, budgets=[T] * 4, sel_group=1, seed=0)
-    sample = [(0, 0), (1, 13), (2, 31), (3, 7), (3, 20)]
+    sample = [(0, 0), (0, 19), (0, 31), (1, 4), (1, 13), (1, 26), (2, 9), (2, 22), (2, 31), (3, 0), (3, 7), (3, 20)]
     nd = _check_sample(oracle, U, lay, q, k, v, mod, cu, sample, O=64, R=64, T_of=lambda b: T, G=1, sel_group=1,
                        dec=dec, what=f"7b_16k@{budget}")
     print(f"[full] keys differing near the threshold: {nd}", flush=True)
