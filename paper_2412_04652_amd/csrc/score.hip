@@ -120,6 +120,15 @@ struct QFrags<bf16_tag, D, NQB, false> {
             }
     }
     __device__ __forceinline__ bf16x8 get(int nb, int s, int /*lane*/, const float* /*q_lds*/) const { return f[nb][s]; }
+    // The fragments have landed when this returns.  Called before the tile loop: loads still
+    // pending at the loop's entry make the compiler wait for everything (the prefetched tiles
+    // too) at the fragments' first use, on every iteration.
+    __device__ __forceinline__ void settle() const {
+#pragma unroll
+        for (int nb = 0; nb < NQB; ++nb)
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) asm volatile("" ::"v"(f[nb][s]));
+    }
     static constexpr int kLdsBytes = 0;
 };
 
@@ -147,6 +156,7 @@ struct QFrags<bf16_tag, D, NQB, true> {
     __device__ __forceinline__ bf16x8 get(int nb, int s, int lane, const float* q_lds) const {
         return reinterpret_cast<const bf16x8*>(q_lds)[(nb * NK + s) * 64 + lane];
     }
+    __device__ __forceinline__ void settle() const {}
     static constexpr int kLdsBytes = NQB * NK * 64 * 16;
 };
 
@@ -165,6 +175,7 @@ struct QFrags<f32_tag, D, NQB, IN_LDS> {
     __device__ __forceinline__ float get(int nb, int s, int lane, const float* q_lds) const {
         return q_lds[(nb * 32 + (lane & 31)) * Geom<f32_tag, D>::QSTRIDE + s * 2 + (lane >> 5)];
     }
+    __device__ __forceinline__ void settle() const {}
     static constexpr int kLdsBytes = NQB * 32 * Geom<f32_tag, D>::QSTRIDE * 4;
 };
 
@@ -364,6 +375,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     QF qf;
     qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
     if constexpr (QF::kLdsBytes > 0) __syncthreads();
+    qf.settle();
     if (ntiles > 0) {
     for (int t0 = 0; t0 < ntiles; t0 += PF) {
 #pragma unroll
@@ -547,8 +559,8 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
         if (ntiles > 0) {
 #pragma unroll
             for (int u = 0; u < PF; ++u) {
+                kmod[u] = load_mod(tile_key(u));  // before its tile: the oldest load is the cheapest to wait for
                 load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(u), L, lane);
-                kmod[u] = load_mod(tile_key(u));
             }
         }
         __syncthreads();  // previous head's nlse_s / q_lds are no longer read
@@ -584,6 +596,7 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
         QF qf;
         qf.load(reinterpret_cast<const char*>(p.q_win) + ((size_t)(b * p.H_q + hq) * O) * D * G::EB, O, tid, q_lds);
         __syncthreads();  // nlse_s (and staged queries) visible
+        qf.settle();
         if (ntiles > 0) {
         for (int t0 = 0; t0 < ntiles; t0 += PF) {
 #pragma unroll
@@ -598,8 +611,8 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
                 }
                 const bool key_text = kmod[u] == 0;
                 // one tile of loads per iteration on every path (see the ring in pass A)
-                load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
                 kmod[u] = load_mod(tile_key(t + PF));
+                load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_key(t + PF), L, lane);
                 if (!live) continue;
 
                 // the accumulator starts at -lse_i/c, so that 2^(c*acc) is the normalised weight
