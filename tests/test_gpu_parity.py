@@ -549,6 +549,35 @@ def test_end_to_end_edge_cases(gpu, oracle, name):
     _end_to_end(U, oracle, case, [(b, s) for b in range(case.B) for s in range(H_sel)], 2)
 
 
+@pytest.mark.parametrize("dtype,L", [("bf16", 1500), ("f32", 700), ("bf16", 5000)])
+def test_all_scores_tie_lower_index_wins(gpu, oracle, dtype, L):
+    """Zero queries: every logit is 0, so all prefix keys of a modality carry the same score (the
+    same sum of 1/(visible keys) over the window rows) and the selection is decided by the tie rule
+    alone: the lowest indices of each region, exactly as in the oracle."""
+    U = _util()
+    n_vis = L // 2
+    case = W.make_case("ties", dtype=dtype, H_q=2, H_kv=2, D=64, O=16, R=16,
+                       layouts=[[(0, 100), (1, n_vis), (0, L - 100 - n_vis)]], budgets=[L // 3], seed=3)
+    case.q_win[...] = 0
+    dc = U.DeviceCase(case)
+    dc.layer.prune(dc.q_win, dc.k, dc.v, dc.modality)
+    torch.cuda.synchronize()
+    g_self = dc.layer.score_self.cpu().numpy()
+    g_cross = dc.layer.score_cross.cpu().numpy()
+    P = L - 16
+    mod = case.modality
+    for h in range(2):
+        # identical bits within each region: the tie is exact on the GPU too
+        assert len(np.unique(g_self[h, :P][mod[:P] == 0])) == 1 and len(np.unique(g_cross[h, :P][mod[:P] == 1])) == 1
+        res = oracle.prune_group(case, 0, h)
+        n = int(dc.layer.kept_cnt[0, h, 0])
+        np.testing.assert_array_equal(dc.layer.kept_idx[0, h, :n].cpu().numpy(), res["idx"])
+        K_s, K_c = res["counts"]["K_s"], res["counts"]["K_c"]
+        text, vis = np.flatnonzero(mod[:P] == 0), np.flatnonzero(mod[:P] == 1)
+        expect = np.sort(np.concatenate([text[:K_s], vis[:K_c], np.arange(P, L)]))
+        np.testing.assert_array_equal(res["idx"], expect)
+
+
 def test_compact_token_major_input(gpu, oracle):
     """K and V stored [tokens, H_kv, D]: same pruned cache as from the head-major layout."""
     U = _util()
