@@ -578,6 +578,25 @@ def test_all_scores_tie_lower_index_wins(gpu, oracle, dtype, L):
         np.testing.assert_array_equal(res["idx"], expect)
 
 
+@pytest.mark.parametrize("dtype,scale", [("bf16", 8.0), ("f32", 16.0), ("bf16", 0.03125)])
+def test_sharp_and_flat_softmax_end_to_end(gpu, oracle, dtype, scale):
+    """Queries scaled by a power of two (exact in both storage types): logits with a standard deviation
+    of about 8 or 16 (rows close to one-hot, most weights far below the fp32 normal range of the
+    sums) and of about 0.03 (rows close to uniform, scores nearly tied)."""
+    U = _util()
+    case = W.make_case("sharp", dtype=dtype, H_q=4, H_kv=2, D=128, O=32, R=32, sel_group=2,
+                       layouts=[[(0, 300), (1, 1400), (0, 500)], [(1, 900), (0, 140)]], budgets=[700, 300], seed=17,
+                       decode_steps=2)
+    if dtype == "bf16":
+        for name in ("q_win", "dec_q"):
+            a = getattr(case, name)
+            a[...] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(a) * np.float32(scale))
+    else:
+        case.q_win *= np.float32(scale)
+        case.dec_q *= np.float32(scale)
+    _end_to_end(U, oracle, case, [(b, s) for b in range(2) for s in range(2)], 2)
+
+
 def test_compact_token_major_input(gpu, oracle):
     """K and V stored [tokens, H_kv, D]: same pruned cache as from the head-major layout."""
     U = _util()
