@@ -15,7 +15,7 @@
 // The two orientations use the same LDS tile and the same register fragments;
 // only the operand order of the MFMA differs.
 // A workgroup is 4 wavefronts that take the 32-key tiles of the workgroup's
-// chunk round-robin, in a rotated order; a tile is streamed with coalesced 16-byte
+// chunk round-robin; a tile is streamed with coalesced 16-byte
 // global loads (4 full 256-byte rows per instruction for bf16/D=128) into a
 // ring of register tiles PF tiles ahead (the loop is bound by HBM latency: the
 // bytes in flight per compute unit, not the arithmetic, set the rate), a
@@ -357,15 +357,12 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_A : 1) void scor
     // the same on every path and the wait before a tile is used covers that tile only.
     constexpr int PF = Prefetch<E>::A;
     u32x4 st[PF][G::NLD];
-    // Tiles are visited in a rotated order (tile (t + rot) mod ntiles at step t) with a
-    // different rotation per wavefront and workgroup: all key runs are aligned to large powers
-    // of two, and wavefronts walking them in lockstep would hit the same memory channels.
-    // (the query heads of a GQA group share the rotation: they start together on one XCD and
-    // walk the same keys in the same order, so all but the first find a tile in that XCD's L2)
-    const int rot = ntiles > 0 ? (int)((chunk * 5u + hk * 7u + b * 11u) % (unsigned)ntiles) : 0;
+    // Tiles are visited in ascending order (the query heads of a GQA group start together on one
+    // XCD and walk the same keys in the same order, so all but the first find a tile in that
+    // XCD's L2).  A per-workgroup rotation of the order, once needed against channel camping with
+    // many small chunks, measures no better with 512 large chunks.
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
-        const int tt = t + rot;
-        return t < ntiles ? walk.base + (tt < ntiles ? tt : tt - ntiles) * walk.stride : L - 1;
+        return t < ntiles ? walk.base + t * walk.stride : L - 1;
     };
     // the key stream starts first; the queries (L2-resident, small) follow
     if (ntiles > 0) {
@@ -538,11 +535,8 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     const int64_t tok_bytes = p.k_stride_tok * G::EB;
 
     constexpr int PF = Prefetch<E>::B;
-    // same rotated visiting order as pass A (the two passes need not agree)
-    const int rot = ntiles > 0 ? (int)((chunk * 5u + sg * 7u + b * 11u) % (unsigned)ntiles) : 0;
     auto tile_key = [&](int t) {  // first key of the tile visited at step t (steps past the end: any valid row)
-        const int tt = t + rot;
-        return t < ntiles ? walk.base + (tt < ntiles ? tt : tt - ntiles) * walk.stride : L - 1;
+        return t < ntiles ? walk.base + t * walk.stride : L - 1;
     };
     auto load_mod = [&](int j0) -> uint8_t {  // modality of key j0 + lane%32, fetched with its tile
         const int j = j0 + (lane & 31);
