@@ -135,6 +135,13 @@ int csp_score_lse(const csp_desc* desc, const void* q_win, const void* k, const 
                   const float* row_lse, float* score_self, float* score_cross,
                   void* ws, size_t ws_bytes, void* stream);
 
+/* Test hook for csp_score's single-read path (bf16, O <= 64, sel_group == 1), in which the
+ * workgroups of a head exchange their softmax statistics inside one launch: the longest time a
+ * workgroup waits for the others before it computes the statistics of the whole head by itself,
+ * in 10 ns ticks (default 100000 = 1 ms; 0 = never wait, every workgroup takes the self-sufficient
+ * path).  Results do not depend on the value beyond rounding.  Process-wide; host-side only. */
+void csp_debug_set_score_wait(int64_t ticks);
+
 /* ------------------------------------------------------------------------
  * csp_select — Eq. "top-K" per region, the mask combination (read as the
  * union of the two independently selected sets), the recent keys of the

@@ -12,7 +12,7 @@ _lib = None
 CSP_BF16, CSP_F32 = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "csp_strerror", "csp_version",
+    "csp_strerror", "csp_version", "csp_debug_set_score_wait",
     "csp_score_workspace_bytes", "csp_score", "csp_score_lse",
     "csp_select_workspace_bytes", "csp_select",
     "csp_compact",
@@ -58,6 +58,7 @@ def load_library():
         dp = C.POINTER(_CDesc)
         L.csp_strerror.argtypes = [C.c_int]; L.csp_strerror.restype = C.c_char_p
         L.csp_version.argtypes = []; L.csp_version.restype = C.c_char_p
+        L.csp_debug_set_score_wait.argtypes = [i64]; L.csp_debug_set_score_wait.restype = None
         L.csp_score_workspace_bytes.argtypes = [dp]; L.csp_score_workspace_bytes.restype = sz
         L.csp_select_workspace_bytes.argtypes = [dp]; L.csp_select_workspace_bytes.restype = sz
         L.csp_decode_workspace_bytes.argtypes = [dp, i32]; L.csp_decode_workspace_bytes.restype = sz
@@ -86,6 +87,12 @@ def csp_strerror(code: int) -> str:
 
 def csp_version() -> str:
     return load_library().csp_version().decode()
+
+
+def csp_debug_set_score_wait(ticks: int) -> None:
+    """Test hook: longest wait (10 ns ticks) of the single-read score kernel for the other
+    chunks of a head; 0 makes every workgroup take its self-sufficient path."""
+    load_library().csp_debug_set_score_wait(C.c_int64(int(ticks)))
 
 
 class Desc:

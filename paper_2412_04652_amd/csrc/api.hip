@@ -1,6 +1,7 @@
 // C ABI of libcsp: host-side validation and marshalling (see include/csp.h for
 // the contract of every entry point).  Nothing here touches the GPU until the
 // arguments have been checked.
+#include <atomic>
 #include <cmath>
 #include <cstring>
 
@@ -89,19 +90,20 @@ const char* csp_strerror(int code) {
 
 const char* csp_version(void) { return "csp-gfx950 0.1"; }
 
+// longest wait of a one-pass score workgroup for the other chunks of its head (10 ns ticks)
+static std::atomic<int64_t> g_score_spin_ticks{100000};
+
+void csp_debug_set_score_wait(int64_t ticks) { g_score_spin_ticks.store(ticks < 0 ? 0 : ticks); }
+
 size_t csp_score_workspace_bytes(const csp_desc* d) {
-    Checked c;
     if (!d || d->B <= 0 || d->H_q <= 0 || d->max_seqlen <= 0 || d->window_O <= 0) return 0;
-    const int ck = score_chunk_keys(d->B, d->H_q, d->max_seqlen, d->dtype, d->D, d->window_O);
-    const size_t n_chunks = (size_t)(d->max_seqlen + ck - 1) / ck;
-    (void)c;
-    size_t bytes = (size_t)d->B * d->H_q * n_chunks * d->window_O * 2 * sizeof(float);
+    if (d->sel_group <= 0 || d->H_q % d->sel_group != 0) return 0;
+    const ScorePlan pl = score_plan(d->B, d->H_q, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, false);
+    size_t bytes = pl.part_bytes;
     // per-slice sums of a selection group that is split over several workgroups
-    if (d->sel_group > 1 && d->H_q % d->sel_group == 0) {
-        const int gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, (int)n_chunks);
-        const int gsplit = (d->sel_group + gper - 1) / gper;
+    if (pl.gsplit > 1) {
         const size_t total = d->cu_seqlens_host ? (size_t)d->cu_seqlens_host[d->B] : (size_t)d->B * d->max_seqlen;
-        if (gsplit > 1) bytes = ((bytes + 15) & ~(size_t)15) + (size_t)2 * gsplit * (d->H_q / d->sel_group) * total * sizeof(float);
+        bytes += (size_t)2 * pl.gsplit * (d->H_q / d->sel_group) * total * sizeof(float);
     }
     return bytes;
 }
@@ -128,14 +130,15 @@ static int score_common(const csp_desc* d, const void* q_win, const void* k, con
     p.score_elems = (int64_t)c.H_sel * c.total_tokens;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
-    p.chunk_keys = score_chunk_keys(d->B, d->H_q, d->max_seqlen, d->dtype, d->D, d->window_O);
-    p.n_chunks = (d->max_seqlen + p.chunk_keys - 1) / p.chunk_keys;
+    const ScorePlan pl = score_plan(d->B, d->H_q, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, row_lse != nullptr);
+    p.fused = pl.fused ? 1 : 0;
+    p.arrive = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + pl.off_arrive);
+    p.spin_ticks = g_score_spin_ticks.load();
+    p.chunk_keys = pl.chunk_keys; p.n_chunks = pl.n_chunks;
     p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
-    p.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, p.n_chunks);
-    p.gsplit = (d->sel_group + p.gper - 1) / p.gper;
+    p.gper = pl.gper; p.gsplit = pl.gsplit;
     if (p.gsplit > 1) {
-        const size_t base = ((size_t)d->B * d->H_q * p.n_chunks * d->window_O * 2 * sizeof(float) + 15) & ~(size_t)15;
-        p.slice_self = reinterpret_cast<float*>(static_cast<char*>(ws) + base);
+        p.slice_self = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_bytes);
         p.slice_cross = p.slice_self + (size_t)p.gsplit * (d->H_q / d->sel_group) * c.total_tokens;
     }
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
@@ -318,19 +321,16 @@ int csp_window_push(const csp_desc* d, const void* q_new, void* q_ring, int32_t 
 
 namespace {
 struct RepruneLayout {
-    int chunk_keys, n_chunks, gper, gsplit;
+    ScorePlan plan;
     size_t off_part, off_slices, total;
 };
 RepruneLayout reprune_layout(const csp_desc* d, int H_sel, int row_bytes, int cache_cap) {
     RepruneLayout l;
-    l.chunk_keys = score_chunk_keys(d->B, d->H_q, cache_cap, d->dtype, d->D, d->window_O);
-    l.n_chunks = (cache_cap + l.chunk_keys - 1) / l.chunk_keys;
-    l.gper = score_heads_per_slice(d->B, d->H_q, d->sel_group, l.n_chunks);
-    l.gsplit = (d->sel_group + l.gper - 1) / l.gper;
+    l.plan = score_plan(d->B, d->H_q, d->sel_group, cache_cap, d->dtype, d->D, d->window_O, false);
     auto up = [](size_t x) { return (x + 15) & ~(size_t)15; };
     l.off_part = up((size_t)d->B * d->H_q * d->window_O * row_bytes);                  // the window in temporal order
-    l.off_slices = l.off_part + up((size_t)d->B * d->H_q * l.n_chunks * d->window_O * 2 * sizeof(float));
-    l.total = l.off_slices + (l.gsplit > 1 ? (size_t)2 * l.gsplit * d->B * H_sel * cache_cap * sizeof(float) : 0);
+    l.off_slices = l.off_part + l.plan.part_bytes;
+    l.total = l.off_slices + (l.plan.gsplit > 1 ? (size_t)2 * l.plan.gsplit * d->B * H_sel * cache_cap * sizeof(float) : 0);
     return l;
 }
 }  // namespace
@@ -387,10 +387,13 @@ int csp_reprune(const csp_desc* d, const void* q_ring, int32_t ring_start, void*
     p.score_elems = (int64_t)d->B * c.H_sel * cache_cap;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
-    p.chunk_keys = l.chunk_keys; p.n_chunks = l.n_chunks; p.gper = l.gper; p.gsplit = l.gsplit;
-    if (l.gsplit > 1) {
+    p.fused = l.plan.fused ? 1 : 0;
+    p.arrive = reinterpret_cast<int32_t*>(wsb + l.off_part + l.plan.off_arrive);
+    p.spin_ticks = g_score_spin_ticks.load();
+    p.chunk_keys = l.plan.chunk_keys; p.n_chunks = l.plan.n_chunks; p.gper = l.plan.gper; p.gsplit = l.plan.gsplit;
+    if (l.plan.gsplit > 1) {
         p.slice_self = reinterpret_cast<float*>(wsb + l.off_slices);
-        p.slice_cross = p.slice_self + (size_t)l.gsplit * p.score_elems;
+        p.slice_cross = p.slice_self + (size_t)l.plan.gsplit * p.score_elems;
     }
     p.k_stride_tok = cache_stride_tok; p.k_stride_head = cache_stride_head;
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));

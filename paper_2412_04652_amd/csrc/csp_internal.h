@@ -73,7 +73,11 @@ struct ScoreParams {
     const uint8_t* modality;
     float* score_self;
     float* score_cross;
-    float* part;          // [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units
+    float* part;          // two passes: [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units;
+                          // one pass: [B][H_q][n_chunks][O] log-sum-exp of a chunk in log2 units
+    int32_t* arrive;      // one pass: [B][H_q] chunks of the head that have published their statistics
+    int64_t spin_ticks;   // one pass: longest wait for the other chunks, in 10 ns ticks; 0 = do not wait
+    int32_t fused;        // 1: one pass over the keys (score_plan decides)
     const float* row_lse; // [B][H_q][O] natural-log normaliser of every window row, supplied by the caller
                           // (then the statistics pass is skipped and `part` is not used); nullptr otherwise
     float* slice_self;    // [gsplit][score_elems] per-slice sums of a split selection group (gsplit > 1)
@@ -185,6 +189,13 @@ hipError_t launch_window_push(const WindowParams& p, hipStream_t s);
 hipError_t launch_window_unroll(const WindowParams& p, hipStream_t s);
 
 // host-side sizing rules shared by the *_workspace_bytes functions and the launchers
+struct ScorePlan {
+    bool fused;            // statistics and column sums from one read of the keys
+    int chunk_keys, n_chunks, gper, gsplit;
+    size_t part_bytes;     // statistics region at the start of the workspace (16-byte multiple)
+    size_t off_arrive;     // one pass: offset of the arrival counters inside that region
+};
+ScorePlan score_plan(int B, int H_q, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse);
 int score_chunk_keys(int B, int H_q, int max_seqlen, int dtype, int D, int O);
 // heads of a selection group that one workgroup of the column-sum pass sums itself
 int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks);

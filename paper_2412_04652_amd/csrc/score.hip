@@ -137,21 +137,33 @@ struct QFrags<bf16_tag, D, NQB, false> {
 template <int D, int NQB>
 struct QFrags<bf16_tag, D, NQB, true> {
     static constexpr int NK = D / 16;
-    __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* q_lds) {
-        constexpr int N = NQB * NK * 64;                      // 16-byte pieces in all
-        constexpr int IT = (N + kThreads - 1) / kThreads;     // ... per thread
-        u32x4 w[IT];
+    static constexpr int N = NQB * NK * 64;                      // 16-byte pieces in all
+    static constexpr int IT = (N + kThreads - 1) / kThreads;     // ... per thread
+    // Staging in two steps, so that a caller can put other loads between them: issue() starts
+    // the global loads into w, commit() writes them to LDS (the caller barriers afterwards).
+    // Every lane loads (rows past the window re-read its last row and are zeroed in commit):
+    // a load under a branch makes the compiler wait for every load in flight.
+    __device__ __forceinline__ void issue(u32x4 (&w)[IT], const char* qhead, int O, int tid) const {
 #pragma unroll
-        for (int k = 0; k < IT; ++k) {                // all loads first, then all LDS writes
-            const int e = tid + k * kThreads;
+        for (int k = 0; k < IT; ++k) {
+            const int e = min(tid + k * kThreads, N - 1);
             const int l = e & 63, s = (e >> 6) % NK, nb = e / (64 * NK);
             const int row = nb * 32 + (l & 31);
-            w[k] = u32x4{0u, 0u, 0u, 0u};
-            if (e < N && row < O) w[k] = *reinterpret_cast<const u32x4*>(qhead + ((size_t)row * D + s * 16 + (l >> 5) * 8) * 2);
+            w[k] = *reinterpret_cast<const u32x4*>(qhead + ((size_t)min(row, O - 1) * D + s * 16 + (l >> 5) * 8) * 2);
         }
+    }
+    __device__ __forceinline__ void commit(const u32x4 (&w)[IT], int O, int tid, float* q_lds) const {
 #pragma unroll
-        for (int k = 0; k < IT; ++k)
-            if (tid + k * kThreads < N) reinterpret_cast<u32x4*>(q_lds)[tid + k * kThreads] = w[k];
+        for (int k = 0; k < IT; ++k) {
+            const int e = tid + k * kThreads;
+            const int row = (e / (64 * NK)) * 32 + (e & 31);
+            if (e < N) reinterpret_cast<u32x4*>(q_lds)[e] = row < O ? w[k] : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+    __device__ __forceinline__ void load(const char* qhead, int O, int tid, float* q_lds) {
+        u32x4 w[IT];
+        issue(w, qhead, O, tid);
+        commit(w, O, tid, q_lds);
     }
     __device__ __forceinline__ bf16x8 get(int nb, int s, int lane, const float* q_lds) const {
         return reinterpret_cast<const bf16x8*>(q_lds)[(nb * NK + s) * 64 + lane];
@@ -667,6 +679,451 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
     }
 }
 
+// ---------------------------------------------------------------------------
+// One pass: statistics and column sums from a single read of the keys.
+// ---------------------------------------------------------------------------
+// A workgroup owns kFusedChunk keys and keeps their logits against the whole window in its
+// accumulator registers (kFusedTiles tiles of 32 keys per wavefront).  It publishes the
+// log-sum-exp of its chunk for every window row, waits until the other chunks of the same head
+// have done so, and turns its registers into normalised weights: no second walk over the keys.
+// The exchange uses agent-scope atomic stores and loads (write-through / read-through at the
+// level the XCDs share) and a counter per head; no release fence, which on this part would
+// write back a whole L2.  Workgroups start in the order of their linear id and the chunks of
+// a head have consecutive ids, so the workgroups waited for are already running; the wait is
+// bounded all the same, and a workgroup that gives up computes the row statistics of the whole
+// head by itself (stats_whole_head), so the kernel ends whatever the scheduling.
+#ifndef CSP_FUSED_TILES
+#define CSP_FUSED_TILES 4
+#endif
+constexpr int kFusedTiles = CSP_FUSED_TILES;
+constexpr int kFusedOccupancy = kFusedTiles <= 3 ? 3 : 2;  // workgroups per compute unit the registers allow
+// query fragments of the one-pass kernel: LDS in operand order (1) or registers (0); with the
+// chunk's logits held in 32 * kFusedTiles registers per 32 window rows, registers are the scarce side
+#ifndef CSP_FUSED_Q_LDS
+#define CSP_FUSED_Q_LDS 1
+#endif
+constexpr bool kFusedQLds = CSP_FUSED_Q_LDS != 0;
+constexpr int kFusedChunk = kWaves * kTile * kFusedTiles;
+// int32 slots between the arrival counters of two heads: each counter is polled by the waiting
+// workgroups of its head, and neighbours in one 256-byte line would load one memory channel
+constexpr int kArriveStride = 64;
+#ifndef CSP_FUSED_POLL_SLEEP
+#define CSP_FUSED_POLL_SLEEP 16
+#endif
+
+// LDS of the one-pass kernel.  The exchange buffers live inside the key tiles, which are dead once
+// a wavefront has its logits: `red` row w in the first 512 bytes of wavefront w's own tile (a
+// wavefront writes it right after its own last MFMA, while others may still read their tiles),
+// the chunk's scores at the start of the tile area (written after several workgroup barriers).
+template <typename E, int D, int NQB>
+struct FusedSmem {
+    using G = Geom<E, D>;
+    static constexpr int NQ = NQB * 32;
+    static constexpr int kTiles = kWaves * G::TILE_LDS;
+    static constexpr int off_sc = 0;                               // float [2][kFusedChunk], aliases the tiles
+    static constexpr int off_rowm = kTiles;                        // float [NQ] chunk maximum of every row
+    static constexpr int off_f = off_rowm + NQ * 4;                // float [NQ] 2^(chunk maximum - lse)
+    static constexpr int off_wq = off_f + NQ * 4;                  // uint8 [NQ]
+    static constexpr int off_flag = off_wq + NQ;                   // int [2]: all chunks arrived; modalities in the window
+    static constexpr int off_q = (off_flag + 8 + 15) & ~15;        // queries in operand order
+    static constexpr int total = off_q + QFrags<E, D, NQB, true>::kLdsBytes;
+    static_assert(2 * kFusedChunk * 4 <= kTiles && 64 * 8 <= G::TILE_LDS, "exchange buffers must fit in the tiles");
+    // float2 [64] of wavefront w
+    __device__ static float2* red_row(char* smem, int w) { return reinterpret_cast<float2*>(smem + w * G::TILE_LDS); }
+};
+
+// x[r], r < N, holds this lane's value for register index r; on return lane l holds the
+// reduction over the 32 lanes of its half for r = l % N (N == 16: lanes l and l^16 both).
+template <int N, int W, bool MAX>
+__device__ __forceinline__ void reduce_scatter_step(float (&x)[N], int lane) {
+    // lanes l and l^W split values 0..2W-1 between them: the lane with bit W set keeps the upper W
+    const bool up = (lane & W) != 0;
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+        const float send = up ? x[k] : x[k + W];
+        const float keep = up ? x[k + W] : x[k];
+        const float recv = __shfl_xor(send, W);
+        x[k] = MAX ? fmaxf(keep, recv) : keep + recv;
+    }
+    if constexpr (W > 1) reduce_scatter_step<N, W / 2, MAX>(x, lane);
+}
+template <int N, bool MAX>
+__device__ __forceinline__ float reduce_scatter(float (&x)[N], int lane) {
+    reduce_scatter_step<N, N / 2, MAX>(x, lane);
+    float r = x[0];
+    if constexpr (N == 16) {
+        const float o = __shfl_xor(r, 16);
+        r = MAX ? fmaxf(r, o) : r + o;
+    }
+    return r;
+}
+
+// (max, sum-exp) in log2 units of every window row over all L keys of one head, computed by
+// this workgroup alone; thread i < NQ returns the statistics of row i.
+template <typename E, int D, int NQB>
+__device__ __forceinline__ float2 stats_whole_head(const ScoreParams& p, const char* kbase, int64_t tok_bytes, const char* qhead,
+                                                int L, char* smem) {
+    using G = Geom<E, D>;
+    using SM = FusedSmem<E, D, NQB>;
+    using QF = QFrags<E, D, NQB, true>;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+    const float NEG_INF = -__builtin_inff();
+    char* tile = smem + wave * G::TILE_LDS;
+    float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
+    QF qf;
+    qf.load(qhead, p.O, tid, q_lds);
+    __syncthreads();
+    float m_run[NQB], l_run[NQB];
+    int pos_q[NQB];
+#pragma unroll
+    for (int nb = 0; nb < NQB; ++nb) {
+        m_run[nb] = NEG_INF;
+        l_run[nb] = 0.f;
+        pos_q[nb] = L - p.O + nb * 32 + (lane & 31);
+    }
+    for (int j0 = wave * kTile; j0 < L; j0 += kWaves * kTile) {
+        u32x4 st[G::NLD];
+        load_tile<E, D, false>(st, kbase, tok_bytes, j0, L, lane);
+        wave_lds_sync();
+        store_tile<E, D>(st, tile, lane);
+        wave_lds_sync();
+        f32x16 acc[NQB];
+#pragma unroll
+        for (int nb = 0; nb < NQB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < G::NK; ++s) {
+            const auto kf = k_frag<E, D>(tile, s, lane);
+#pragma unroll
+            for (int nb = 0; nb < NQB; ++nb) acc[nb] = mma(kf, qf.get(nb, s, lane, q_lds), acc[nb]);
+        }
+        stats_tile<NQB, true>(acc, p.scale_log2, j0, half, L, p.causal, pos_q, m_run, l_run);
+    }
+#pragma unroll
+    for (int nb = 0; nb < NQB; ++nb) {
+        const float mo = __shfl_xor(m_run[nb], 32);
+        const float lo = __shfl_xor(l_run[nb], 32);
+        const float M = fmaxf(m_run[nb], mo);
+        const float Ms = M == NEG_INF ? 0.f : M;
+        const float Lc = l_run[nb] * fast_exp2(m_run[nb] - Ms) + lo * fast_exp2(mo - Ms);
+        if (half == 0) SM::red_row(smem, wave)[nb * 32 + lane] = make_float2(M, Lc);
+    }
+    __syncthreads();
+    float2 out = make_float2(NEG_INF, 0.f);
+    if (tid < NQB * 32) {
+        float M = NEG_INF;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) M = fmaxf(M, SM::red_row(smem, w)[tid].x);
+        const float Ms = M == NEG_INF ? 0.f : M;
+        float Lc = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float2 r = SM::red_row(smem, w)[tid];
+            Lc += r.y * fast_exp2(r.x - Ms);
+        }
+        out = make_float2(M, Lc);
+    }
+    __syncthreads();  // the tiles are reused by the caller
+    return out;
+}
+
+__global__ __launch_bounds__(256) void score_fused_clear_kernel(ScoreParams p) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < p.B * p.H_q) p.arrive[(size_t)i * kArriveStride] = 0;
+}
+
+template <typename E, int D, int NQB>
+__global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(ScoreParams p) {
+    using G = Geom<E, D>;
+    using QF = QFrags<E, D, NQB, kFusedQLds>;
+    using SM = FusedSmem<E, D, NQB>;
+    constexpr int NQ = NQB * 32, N = NQB * 16, NT = kFusedTiles;
+    extern __shared__ __align__(16) char smem[];
+    // one head per selection group, so no GQA: query head = KV head.  task = (chunk, head, sequence),
+    // the first index fastest: the chunks of a head have consecutive workgroup ids
+    int task = blockIdx.x;
+    if (task >= p.n_chunks * p.H_q * p.B) return;
+    const int chunk = task % p.n_chunks; task /= p.n_chunks;
+    const int hq = task % p.H_q, b = task / p.H_q;
+    const int hk = hq;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
+    const int L = view_len(p.view, b, hk);
+    const int c0 = chunk * kFusedChunk;
+    if (c0 >= L || view_fits(p.view, b, L)) return;
+    const int O = p.O, R = p.R;
+    const float c = p.scale_log2;
+    const float NEG_INF = -__builtin_inff();
+    const int n_chunks_b = (L + kFusedChunk - 1) / kFusedChunk;  // chunks of this sequence that publish statistics
+    const int bh = b * p.H_q + hq;
+    const uint8_t* const mod = p.modality + view_mod0(p.view, b, hq);  // one head per selection group here
+    const size_t score0 = (size_t)view_score0(p.view, b, hq);
+
+    char* tile = smem + wave * G::TILE_LDS;
+    float* rowm = reinterpret_cast<float*>(smem + SM::off_rowm);
+    float* f_s = reinterpret_cast<float*>(smem + SM::off_f);
+    float* sc_lds = reinterpret_cast<float*>(smem + SM::off_sc);
+    uint8_t* wq = reinterpret_cast<uint8_t*>(smem + SM::off_wq);
+    int* flag = reinterpret_cast<int*>(smem + SM::off_flag);
+
+    const char* kbase = reinterpret_cast<const char*>(p.k) + (view_key0(p.view, b, p.k_stride_tok) + (int64_t)hk * p.k_stride_head) * G::EB;
+    const int64_t tok_bytes = p.k_stride_tok * G::EB;
+    const char* qhead = reinterpret_cast<const char*>(p.q_win) + ((size_t)bh * O) * D * G::EB;
+
+    // wavefront w takes tiles w, w+4, w+8, w+12 of the chunk; tiles past the end of the sequence
+    // re-read its last row and are masked out
+    auto tile_j0 = [&](int t) { return c0 + (t * kWaves + wave) * kTile; };
+#ifndef CSP_FUSED_PF
+#define CSP_FUSED_PF 2
+#endif
+    constexpr int PF = CSP_FUSED_PF;
+    u32x4 st[PF][G::NLD];
+    float* q_lds = reinterpret_cast<float*>(smem + SM::off_q);
+    QF qf;
+    const uint8_t wq_mod = mod[L - O + (tid < O ? tid : 0)];  // modality of window row tid
+    if constexpr (kFusedQLds) {
+        // the queries (small, L2-resident) are requested first: loads return in order, so the
+        // wait for them does not include the key tiles requested behind them
+        u32x4 qw[QF::IT];
+        qf.issue(qw, qhead, O, tid);
+#pragma unroll
+        for (int u = 0; u < PF; ++u) load_tile<E, D, false>(st[u], kbase, tok_bytes, tile_j0(u), L, lane);
+        qf.commit(qw, O, tid, q_lds);
+        __syncthreads();
+    } else {
+#pragma unroll
+        for (int u = 0; u < PF; ++u) load_tile<E, D, false>(st[u], kbase, tok_bytes, tile_j0(u), L, lane);
+        qf.load(qhead, O, tid, q_lds);
+        qf.settle();
+    }
+
+    // ---- logits of the chunk: acc[t][mb][v] = q_i . k_j, i = mb*32 + acc_row(v, half), j = tile_j0(t) + lane%32
+    f32x16 acc[NT][NQB];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        wave_lds_sync();
+        store_tile<E, D>(st[t % PF], tile, lane);
+        wave_lds_sync();
+        if (t + PF < NT) load_tile<E, D, false>(st[t % PF], kbase, tok_bytes, tile_j0(t + PF), L, lane);
+#pragma unroll
+        for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][mb][v] = 0.f;
+#pragma unroll
+        for (int s = 0; s < G::NK; ++s) {
+            const auto kf = k_frag<E, D>(tile, s, lane);
+#pragma unroll
+            for (int mb = 0; mb < NQB; ++mb) acc[t][mb] = mma(qf.get(mb, s, lane, q_lds), kf, acc[t][mb]);
+        }
+    }
+    if (tid < NQ) wq[tid] = tid < O ? (wq_mod ? 1 : 0) : 2;
+    if (wave == 0) {  // does the window hold text rows, visual rows (bits 0, 1)
+        const bool t = __ballot(tid < O && wq_mod == 0) != 0, v = __ballot(tid < O && wq_mod != 0) != 0;
+        if (lane == 0) flag[1] = (t ? 1 : 0) | (v ? 2 : 0);
+    }
+    // keys past the end, and keys a row may not see (causal tail)
+    if (c0 + kFusedChunk > (p.causal ? L - O : L)) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int j = tile_j0(t) + (lane & 31);
+#pragma unroll
+            for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int i = mb * 32 + acc_row(v, half);
+                    const bool ok = j < L && (!p.causal || j <= L - O + i);
+                    acc[t][mb][v] = ok ? acc[t][mb][v] : NEG_INF;
+                }
+        }
+    }
+
+    // ---- chunk statistics of every row: maximum, then sum of 2^(x - maximum)
+    const int my_row = ((lane & (N - 1)) >> 4) * 32 + acc_row(lane & 15, half);  // row this lane ends up with after a reduce_scatter
+    {
+        float rm[N];
+#pragma unroll
+        for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float m = acc[0][mb][v];
+#pragma unroll
+                for (int t = 1; t < NT; ++t) m = fmaxf(m, acc[t][mb][v]);
+                rm[mb * 16 + v] = m;
+            }
+        wave_lds_sync();  // this wavefront's last tile has been read
+        SM::red_row(smem, wave)[my_row].x = reduce_scatter<N, true>(rm, lane) * c;
+    }
+    __syncthreads();
+    if (tid < NQ) {
+        float M = SM::red_row(smem, 0)[tid].x;
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) M = fmaxf(M, SM::red_row(smem, w)[tid].x);
+        rowm[tid] = M == NEG_INF ? 0.f : M;   // a row that sees no key of the chunk: every weight is 0 anyway
+    }
+    __syncthreads();
+    {
+        float rs[N];
+#pragma unroll
+        for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const float4 w = *reinterpret_cast<const float4*>(rowm + mb * 32 + v4 * 8 + half * 4);
+                const float ms[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int v = v4 * 4 + u;
+                    float sum = 0.f;
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        acc[t][mb][v] = fast_exp2(fmaf(acc[t][mb][v], c, -ms[u]));
+                        sum += acc[t][mb][v];
+                    }
+                    rs[mb * 16 + v] = sum;
+                }
+            }
+        SM::red_row(smem, wave)[my_row].y = reduce_scatter<N, false>(rs, lane);
+    }
+    // modality of this lane's key in every tile: needed after the exchange, lands during the wait
+    uint8_t kmod[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int j = tile_j0(t) + (lane & 31);
+        kmod[t] = mod[j < L ? j : L - 1];
+    }
+    __syncthreads();
+    if (tid < NQ) {
+        float l = SM::red_row(smem, 0)[tid].y;
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) l += SM::red_row(smem, w)[tid].y;
+        // log-sum-exp of the chunk (-inf when the row sees none of its keys)
+        const float lse_c = l > 0.f ? rowm[tid] + fast_log2(l) : NEG_INF;
+        if (tid < O) __hip_atomic_store(p.part + ((size_t)bh * p.n_chunks + chunk) * O + tid, lse_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (wave == 0) {
+        // the stores above have reached the level the XCDs share before the counter moves
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (lane == 0) {
+            int32_t* const counter = p.arrive + (size_t)bh * kArriveStride;
+            // the returned count is the first look at the counter: the last chunk to arrive never polls
+            int seen = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+            int ok = p.spin_ticks > 0;
+            if (ok && seen < n_chunks_b) {
+                const uint64_t t_start = wall_clock64();
+                do {
+                    __builtin_amdgcn_s_sleep(CSP_FUSED_POLL_SLEEP);
+                    if (wall_clock64() - t_start > (uint64_t)p.spin_ticks) { ok = 0; break; }
+                    seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                } while (seen < n_chunks_b);
+            }
+            *flag = ok;
+        }
+    }
+    __syncthreads();
+    const bool have_all = *flag != 0;  // uniform
+    asm volatile("" ::: "memory");
+    float M = NEG_INF, Ls = 0.f;
+    if (have_all) {
+        // merge of the chunks' log-sum-exps: thread (row = tid % 64, quarter = tid / 64) takes every
+        // fourth chunk, all its loads in flight at once; then the four quarters are combined
+        {
+            const int row = tid & 63, quarter = tid >> 6;
+            const float* part = p.part + ((size_t)bh * p.n_chunks) * O + (row < O ? row : 0);
+            for (int ch0 = quarter; ch0 < n_chunks_b; ch0 += 4 * 12) {
+                float r[12];
+#pragma unroll
+                for (int u = 0; u < 12; ++u)
+                    r[u] = ch0 + 4 * u < n_chunks_b ? __hip_atomic_load(part + (size_t)(ch0 + 4 * u) * O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : NEG_INF;
+                float Mn = M;
+#pragma unroll
+                for (int u = 0; u < 12; ++u) Mn = fmaxf(Mn, r[u]);
+                const float Mns = Mn == NEG_INF ? 0.f : Mn;
+                Ls *= fast_exp2(M - Mns);
+#pragma unroll
+                for (int u = 0; u < 12; ++u) Ls += fast_exp2(r[u] - Mns);
+                M = Mn;
+            }
+            SM::red_row(smem, quarter)[row] = make_float2(M, Ls);
+        }
+        __syncthreads();
+        M = NEG_INF; Ls = 0.f;
+        if (tid < NQ) {
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) M = fmaxf(M, SM::red_row(smem, w)[tid].x);   // chunk 0 holds a visible key: finite
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) Ls += SM::red_row(smem, w)[tid].y * fast_exp2(SM::red_row(smem, w)[tid].x - M);
+        }
+    } else {
+        const float2 whole = stats_whole_head<E, D, NQB>(p, kbase, tok_bytes, qhead, L, smem);
+        M = whole.x; Ls = whole.y;
+    }
+    if (tid < NQ) {
+        float f = 0.f;
+        if (tid < O) {
+            Ls += p.n_score * fast_exp2(-M);  // the n of the n-softmax, in the same scaled units
+            f = fast_exp2(rowm[tid] - (M + fast_log2(Ls)));
+        }
+        f_s[tid] = f;
+    }
+    __syncthreads();
+
+    // ---- column sums: weight = 2^(x - chunk maximum) * f_i
+    const bool any_text = (flag[1] & 1) != 0, any_vis = (flag[1] & 2) != 0;
+    const bool mixed = any_text && any_vis;
+    float f[NQB][16];
+#pragma unroll
+    for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const float4 w = *reinterpret_cast<const float4*>(f_s + mb * 32 + v4 * 8 + half * 4);
+            f[mb][v4 * 4 + 0] = w.x; f[mb][v4 * 4 + 1] = w.y; f[mb][v4 * 4 + 2] = w.z; f[mb][v4 * 4 + 3] = w.w;
+        }
+    const int rank_end = L - R;  // keys >= rank_end are not ranked
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        float ct = 0.f, cv = 0.f;  // sums over text / visual window rows
+        if (!mixed) {
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; v += 4) {
+                    s0 = fmaf(acc[t][mb][v], f[mb][v], s0);
+                    s1 = fmaf(acc[t][mb][v + 1], f[mb][v + 1], s1);
+                    s2 = fmaf(acc[t][mb][v + 2], f[mb][v + 2], s2);
+                    s3 = fmaf(acc[t][mb][v + 3], f[mb][v + 3], s3);
+                }
+            ct = (s0 + s1) + (s2 + s3);
+        } else {
+            float t0 = 0.f, t1 = 0.f, v0 = 0.f, v1 = 0.f;
+#pragma unroll
+            for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const bool is_text = wq[mb * 32 + acc_row(v, half)] == 0;
+                    const float pv = acc[t][mb][v] * f[mb][v];
+                    if (v & 1) { t1 += is_text ? pv : 0.f; v1 += is_text ? 0.f : pv; }
+                    else { t0 += is_text ? pv : 0.f; v0 += is_text ? 0.f : pv; }
+                }
+            ct = t0 + t1; cv = v0 + v1;
+        }
+        ct += __shfl_xor(ct, 32);
+        if (mixed) cv += __shfl_xor(cv, 32);
+        else if (any_vis) { cv = ct; ct = 0.f; }  // an all-visual window: every row is a visual query
+        const int j = tile_j0(t) + (lane & 31);
+        const bool key_text = kmod[t] == 0;
+        const float s_self = key_text ? ct : cv;
+        const float s_cross = key_text ? cv : ct;
+        // lanes 0-31 hold the self score of key j, lanes 32-63 its cross score
+        sc_lds[(half ? kFusedChunk : 0) + (j - c0)] = j < rank_end ? (half ? s_cross : s_self) : 0.f;
+    }
+    __syncthreads();
+    const int nk = min(kFusedChunk, L - c0);
+    for (int i = tid; i < nk; i += kThreads) {
+        p.score_self[score0 + c0 + i] = sc_lds[i];
+        p.score_cross[score0 + c0 + i] = sc_lds[kFusedChunk + i];
+    }
+}
+
 // Sum of the per-slice arrays of a split selection group, slices in ascending order
 // (a fixed order: the result does not depend on scheduling).
 __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
@@ -680,7 +1137,24 @@ __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
 }
 
 template <typename E, int D, int NQB>
+hipError_t launch_fused(const ScoreParams& p, hipStream_t s) {
+    if constexpr (NQB <= 2 && elem_bytes<E>::value == 2) {
+        auto k = score_fused_kernel<E, D, NQB>;
+        const unsigned grid = (unsigned)((int64_t)p.n_chunks * p.H_q * p.B);
+        hipLaunchKernelGGL(score_fused_clear_kernel, dim3((unsigned)((p.B * p.H_q + 255) / 256)), dim3(256), 0, s, p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        const size_t smem = FusedSmem<E, D, NQB>::total;
+        hipLaunchKernelGGL(k, dim3(grid), dim3(kThreads), smem, s, p);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;  // excluded by score_plan
+    }
+}
+
+template <typename E, int D, int NQB>
 hipError_t launch_typed(const ScoreParams& p, hipStream_t s) {
+    if (p.fused) return launch_fused<E, D, NQB>(p, s);
     const size_t smem_a = Smem<E, D, NQB, kQaLds>::total, smem_b = Smem<E, D, NQB, kQbLds>::total + (size_t)2 * p.chunk_keys * sizeof(float);
     // keys that several workgroups (GQA) or several head iterations of one workgroup stream stay in L2
     auto ka = p.G > 1 ? score_stats_kernel<E, D, NQB, true> : score_stats_kernel<E, D, NQB, false>;
@@ -745,6 +1219,30 @@ int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks) {
     int gper = sel_group;
     while (gper > 1 && groups * ((sel_group + gper - 1) / gper) < CSP_SCORE_MIN_TASKS) gper = (gper + 1) / 2;
     return gper;
+}
+
+#ifndef CSP_SCORE_FUSED
+#define CSP_SCORE_FUSED 1
+#endif
+ScorePlan score_plan(int B, int H_q, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse) {
+    ScorePlan pl;
+    auto up = [](size_t x) { return (x + 15) & ~(size_t)15; };
+    // two passes over the keys
+    const int ck = score_chunk_keys(B, H_q, max_seqlen, dtype, D, O);
+    const int nc = (max_seqlen + ck - 1) / ck;
+    const size_t two_pass = up((size_t)B * H_q * nc * O * 2 * sizeof(float));
+    // one pass: a log-sum-exp per (head, chunk, row) and an arrival counter per head
+    const int nf = (max_seqlen + kFusedChunk - 1) / kFusedChunk;
+    pl.off_arrive = up((size_t)B * H_q * nf * O * sizeof(float));
+    const size_t one_pass = pl.off_arrive + up((size_t)B * H_q * kArriveStride * sizeof(int32_t));
+    const bool can_fuse = CSP_SCORE_FUSED != 0 && dtype == CSP_BF16 && O <= 64 && sel_group == 1;
+    pl.part_bytes = can_fuse && one_pass > two_pass ? one_pass : two_pass;   // csp_score_lse shares the size
+    pl.fused = can_fuse && !have_row_lse;
+    pl.chunk_keys = pl.fused ? kFusedChunk : ck;
+    pl.n_chunks = pl.fused ? nf : nc;
+    pl.gper = score_heads_per_slice(B, H_q, sel_group, pl.n_chunks);
+    pl.gsplit = (sel_group + pl.gper - 1) / pl.gper;
+    return pl;
 }
 
 hipError_t launch_score(const ScoreParams& p, int dtype, int D, int /*max_seqlen*/, hipStream_t s) {

@@ -63,14 +63,13 @@ SCORE_CASES = {
     "visual_window": dict(layouts=[[(0, 200), (1, 100), (0, 150), (1, 400)]]),
     "mixed_window": dict(layouts=[[(0, 200), (1, 300), (0, 40), (1, 10), (0, 10), (1, 5)]]),
     "long_multi_chunk": dict(layouts=[[(0, 1000), (1, 5000), (0, 777), (1, 2000), (0, 500)]], H_q=1, H_kv=1),
+    "ragged_multi_chunk_d64": dict(H_q=3, H_kv=3, D=64, O=32, R=20, n_score=1.0,
+                                   layouts=[[(0, 40), (1, 1500), (0, 33)], [(1, 513), (0, 32)], [(0, 32)],
+                                            [(0, 3), (1, 1020), (0, 1)]], budgets=[400, 200, 32, 300]),
 }
 
 
-@pytest.mark.parametrize("name", list(SCORE_CASES))
-def test_score_matches_oracle(gpu, oracle, name):
-    U = _util()
-    case = _score_case(name, **SCORE_CASES[name])
-    _say(f"[score] case={name} dtype={case.dtype} D={case.D} O={case.O} R={case.R} lens={np.diff(case.cu_seqlens).tolist()}")
+def _check_score(U, oracle, case, name):
     dc = U.DeviceCase(case)
     dc.layer.score(dc.q_win, dc.k, dc.modality)
     torch.cuda.synchronize()
@@ -85,6 +84,31 @@ def test_score_matches_oracle(gpu, oracle, name):
             U.assert_scores_close(g_self[s, lo:lo + P], a_s[:P], f"{name} b{b} s{s} self")
             U.assert_scores_close(g_cross[s, lo:lo + P], a_c[:P], f"{name} b{b} s{s} cross")
             assert not g_self[s, lo + P:hi].any() and not g_cross[s, lo + P:hi].any()
+
+
+@pytest.mark.parametrize("name", list(SCORE_CASES))
+def test_score_matches_oracle(gpu, oracle, name):
+    U = _util()
+    case = _score_case(name, **SCORE_CASES[name])
+    _say(f"[score] case={name} dtype={case.dtype} D={case.D} O={case.O} R={case.R} lens={np.diff(case.cu_seqlens).tolist()}")
+    _check_score(U, oracle, case, name)
+
+
+@pytest.mark.parametrize("name", ["bf16_d128_o64", "bf16_d64_o32", "o8_r3", "r_zero", "nscore_1", "ragged_batch", "visual_window",
+                                  "mixed_window", "long_multi_chunk", "ragged_multi_chunk_d64"])
+def test_score_single_read_without_waiting(gpu, oracle, name):
+    """The single-read kernel with its wait for the other chunks of a head switched off from the
+    host: every workgroup computes the statistics of the whole head by itself (the path taken
+    when a wait runs out) and the result is the same."""
+    import paper_2412_04652_amd as P
+    U = _util()
+    case = _score_case(name, **SCORE_CASES[name])
+    _say(f"[score, no wait] case={name} dtype={case.dtype} D={case.D} O={case.O} R={case.R}")
+    P.csp_debug_set_score_wait(0)
+    try:
+        _check_score(U, oracle, case, name)
+    finally:
+        P.csp_debug_set_score_wait(100000)
 
 
 def _host_row_lse(oracle, case):
