@@ -245,7 +245,7 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
         prune_gbps=n_layers * (by_score + by_select + by_compact) / (prune_ms * 1e-3) / 1e9,
         ms_per_step=wall / steps * 1e3,
         kernels={
-            "score(2 kernels)": dict(ms=avg(ms["score"]), ms_median=med(ms["score"]), samples=len(ms["score"]),
+            "score": dict(ms=avg(ms["score"]), ms_median=med(ms["score"]), samples=len(ms["score"]),
                                      gbps=by_score / (avg(ms["score"]) * 1e-3) / 1e9, bytes=by_score),
             "select": dict(ms=avg(ms["select"]), ms_median=med(ms["select"]), samples=len(ms["select"]),
                            gbps=by_select / (avg(ms["select"]) * 1e-3) / 1e9, bytes=by_select),
