@@ -1077,6 +1077,15 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
             const float4 w = *reinterpret_cast<const float4*>(f_s + mb * 32 + v4 * 8 + half * 4);
             f[mb][v4 * 4 + 0] = w.x; f[mb][v4 * 4 + 1] = w.y; f[mb][v4 * 4 + 2] = w.z; f[mb][v4 * 4 + 3] = w.w;
         }
+    // bit (mb*16 + v) set: the query of accumulator (mb, v) is a text query (used by mixed windows)
+    uint32_t text_bits = 0u;
+    if (mixed) {
+#pragma unroll
+        for (int mb = 0; mb < NQB; ++mb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (wq[mb * 32 + acc_row(v, half)] == 0) text_bits |= 1u << (mb * 16 + v);
+    }
     const int rank_end = L - R;  // keys >= rank_end are not ranked
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
@@ -1099,7 +1108,7 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
             for (int mb = 0; mb < NQB; ++mb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const bool is_text = wq[mb * 32 + acc_row(v, half)] == 0;
+                    const bool is_text = (text_bits >> (mb * 16 + v)) & 1u;
                     const float pv = acc[t][mb][v] * f[mb][v];
                     if (v & 1) { t1 += is_text ? pv : 0.f; v1 += is_text ? 0.f : pv; }
                     else { t0 += is_text ? pv : 0.f; v0 += is_text ? 0.f : pv; }
