@@ -98,12 +98,12 @@ void csp_debug_set_score_wait(int64_t ticks) { g_score_spin_ticks.store(ticks < 
 size_t csp_score_workspace_bytes(const csp_desc* d) {
     if (!d || d->B <= 0 || d->H_q <= 0 || d->max_seqlen <= 0 || d->window_O <= 0) return 0;
     if (d->sel_group <= 0 || d->H_q % d->sel_group != 0) return 0;
-    const ScorePlan pl = score_plan(d->B, d->H_q, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, false);
+    const ScorePlan pl = score_plan(d->B, d->H_q, d->H_kv, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, false);
     size_t bytes = pl.part_bytes;
     // per-slice sums of a selection group that is split over several workgroups
-    if (pl.gsplit > 1) {
+    if (pl.max_gsplit > 1) {
         const size_t total = d->cu_seqlens_host ? (size_t)d->cu_seqlens_host[d->B] : (size_t)d->B * d->max_seqlen;
-        bytes += (size_t)2 * pl.gsplit * (d->H_q / d->sel_group) * total * sizeof(float);
+        bytes += (size_t)2 * pl.max_gsplit * (d->H_q / d->sel_group) * total * sizeof(float);
     }
     return bytes;
 }
@@ -130,7 +130,7 @@ static int score_common(const csp_desc* d, const void* q_win, const void* k, con
     p.score_elems = (int64_t)c.H_sel * c.total_tokens;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
-    const ScorePlan pl = score_plan(d->B, d->H_q, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, row_lse != nullptr);
+    const ScorePlan pl = score_plan(d->B, d->H_q, d->H_kv, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, row_lse != nullptr);
     p.fused = pl.fused ? 1 : 0;
     p.arrive = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + pl.off_arrive);
     p.spin_ticks = g_score_spin_ticks.load();
@@ -326,11 +326,11 @@ struct RepruneLayout {
 };
 RepruneLayout reprune_layout(const csp_desc* d, int H_sel, int row_bytes, int cache_cap) {
     RepruneLayout l;
-    l.plan = score_plan(d->B, d->H_q, d->sel_group, cache_cap, d->dtype, d->D, d->window_O, false);
+    l.plan = score_plan(d->B, d->H_q, d->H_kv, d->sel_group, cache_cap, d->dtype, d->D, d->window_O, false);
     auto up = [](size_t x) { return (x + 15) & ~(size_t)15; };
     l.off_part = up((size_t)d->B * d->H_q * d->window_O * row_bytes);                  // the window in temporal order
     l.off_slices = l.off_part + l.plan.part_bytes;
-    l.total = l.off_slices + (l.plan.gsplit > 1 ? (size_t)2 * l.plan.gsplit * d->B * H_sel * cache_cap * sizeof(float) : 0);
+    l.total = l.off_slices + (l.plan.max_gsplit > 1 ? (size_t)2 * l.plan.max_gsplit * d->B * H_sel * cache_cap * sizeof(float) : 0);
     return l;
 }
 }  // namespace

@@ -192,10 +192,11 @@ hipError_t launch_window_unroll(const WindowParams& p, hipStream_t s);
 struct ScorePlan {
     bool fused;            // statistics and column sums from one read of the keys
     int chunk_keys, n_chunks, gper, gsplit;
+    int max_gsplit;        // slice arrays the workspace holds (covers csp_score and csp_score_lse)
     size_t part_bytes;     // statistics region at the start of the workspace (16-byte multiple)
     size_t off_arrive;     // one pass: offset of the arrival counters inside that region
 };
-ScorePlan score_plan(int B, int H_q, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse);
+ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse);
 int score_chunk_keys(int B, int H_q, int max_seqlen, int dtype, int D, int O);
 // heads of a selection group that one workgroup of the column-sum pass sums itself
 int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks);

@@ -833,20 +833,26 @@ __global__ __launch_bounds__(256) void score_fused_clear_kernel(ScoreParams p) {
     if (i < p.B * p.H_q) p.arrive[(size_t)i * kArriveStride] = 0;
 }
 
-template <typename E, int D, int NQB>
+template <typename E, int D, int NQB, bool REUSED>
 __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(ScoreParams p) {
     using G = Geom<E, D>;
     using QF = QFrags<E, D, NQB, kFusedQLds>;
     using SM = FusedSmem<E, D, NQB>;
     constexpr int NQ = NQB * 32, N = NQB * 16, NT = kFusedTiles;
     extern __shared__ __align__(16) char smem[];
-    // one head per selection group, so no GQA: query head = KV head.  task = (chunk, head, sequence),
-    // the first index fastest: the chunks of a head have consecutive workgroup ids
-    int task = blockIdx.x;
-    if (task >= p.n_chunks * p.H_q * p.B) return;
+    // task = (query head within its GQA group, chunk, KV head, sequence), the first index fastest:
+    // the chunks of the G heads of a KV head occupy one run of G * n_chunks consecutive workgroup
+    // ids (XCD-aware within it, so that the heads of a group meet in one L2)
+    int task = xcd_task(blockIdx.x, p.G);
+    if (task >= p.G * p.n_chunks * p.view.H_kv * p.B) return;
+    const int g_in = task % p.G; task /= p.G;
     const int chunk = task % p.n_chunks; task /= p.n_chunks;
-    const int hq = task % p.H_q, b = task / p.H_q;
-    const int hk = hq;
+    const int hk = task % p.view.H_kv, b = task / p.view.H_kv;
+    const int hq = hk * p.G + g_in;
+    // selection group of the head; a group of several heads is summed from one array per head
+    const int sg = hq / p.sel_group, slice = hq % p.sel_group;
+    float* const out_self = p.gsplit > 1 ? p.slice_self + (size_t)slice * (size_t)p.score_elems : p.score_self;
+    float* const out_cross = p.gsplit > 1 ? p.slice_cross + (size_t)slice * (size_t)p.score_elems : p.score_cross;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, half = lane >> 5;
     const int L = view_len(p.view, b, hk);
     const int c0 = chunk * kFusedChunk;
@@ -856,8 +862,8 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
     const float NEG_INF = -__builtin_inff();
     const int n_chunks_b = (L + kFusedChunk - 1) / kFusedChunk;  // chunks of this sequence that publish statistics
     const int bh = b * p.H_q + hq;
-    const uint8_t* const mod = p.modality + view_mod0(p.view, b, hq);  // one head per selection group here
-    const size_t score0 = (size_t)view_score0(p.view, b, hq);
+    const uint8_t* const mod = p.modality + view_mod0(p.view, b, sg);
+    const size_t score0 = (size_t)view_score0(p.view, b, sg);
 
     char* tile = smem + wave * G::TILE_LDS;
     float* rowm = reinterpret_cast<float*>(smem + SM::off_rowm);
@@ -887,12 +893,12 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
         u32x4 qw[QF::IT];
         qf.issue(qw, qhead, O, tid);
 #pragma unroll
-        for (int u = 0; u < PF; ++u) load_tile<E, D, false>(st[u], kbase, tok_bytes, tile_j0(u), L, lane);
+        for (int u = 0; u < PF; ++u) load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_j0(u), L, lane);
         qf.commit(qw, O, tid, q_lds);
         __syncthreads();
     } else {
 #pragma unroll
-        for (int u = 0; u < PF; ++u) load_tile<E, D, false>(st[u], kbase, tok_bytes, tile_j0(u), L, lane);
+        for (int u = 0; u < PF; ++u) load_tile<E, D, REUSED>(st[u], kbase, tok_bytes, tile_j0(u), L, lane);
         qf.load(qhead, O, tid, q_lds);
         qf.settle();
     }
@@ -904,7 +910,7 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
         wave_lds_sync();
         store_tile<E, D>(st[t % PF], tile, lane);
         wave_lds_sync();
-        if (t + PF < NT) load_tile<E, D, false>(st[t % PF], kbase, tok_bytes, tile_j0(t + PF), L, lane);
+        if (t + PF < NT) load_tile<E, D, REUSED>(st[t % PF], kbase, tok_bytes, tile_j0(t + PF), L, lane);
 #pragma unroll
         for (int mb = 0; mb < NQB; ++mb)
 #pragma unroll
@@ -1128,8 +1134,8 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
     __syncthreads();
     const int nk = min(kFusedChunk, L - c0);
     for (int i = tid; i < nk; i += kThreads) {
-        p.score_self[score0 + c0 + i] = sc_lds[i];
-        p.score_cross[score0 + c0 + i] = sc_lds[kFusedChunk + i];
+        out_self[score0 + c0 + i] = sc_lds[i];
+        out_cross[score0 + c0 + i] = sc_lds[kFusedChunk + i];
     }
 }
 
@@ -1148,13 +1154,19 @@ __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
 template <typename E, int D, int NQB>
 hipError_t launch_fused(const ScoreParams& p, hipStream_t s) {
     if constexpr (NQB <= 2 && elem_bytes<E>::value == 2) {
-        auto k = score_fused_kernel<E, D, NQB>;
-        const unsigned grid = (unsigned)((int64_t)p.n_chunks * p.H_q * p.B);
+        // the query heads of a GQA group stream the same keys at the same time: plain loads that stay in L2
+        auto k = p.G > 1 ? score_fused_kernel<E, D, NQB, true> : score_fused_kernel<E, D, NQB, false>;
+        const int64_t tasks = (int64_t)p.n_chunks * p.H_q * p.B;
+        const unsigned grid = (unsigned)((tasks + 8 * p.G - 1) / (8 * p.G) * (8 * p.G));
         hipLaunchKernelGGL(score_fused_clear_kernel, dim3((unsigned)((p.B * p.H_q + 255) / 256)), dim3(256), 0, s, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         const size_t smem = FusedSmem<E, D, NQB>::total;
         hipLaunchKernelGGL(k, dim3(grid), dim3(kThreads), smem, s, p);
+        e = hipGetLastError();
+        if (e != hipSuccess || p.gsplit == 1) return e;
+        const size_t n = (size_t)p.score_elems;
+        hipLaunchKernelGGL(score_slice_sum_kernel, dim3((unsigned)((n + 255) / 256), 2), dim3(256), 0, s, p);
         return hipGetLastError();
     } else {
         return hipErrorInvalidValue;  // excluded by score_plan
@@ -1233,7 +1245,7 @@ int score_heads_per_slice(int B, int H_q, int sel_group, int n_chunks) {
 #ifndef CSP_SCORE_FUSED
 #define CSP_SCORE_FUSED 1
 #endif
-ScorePlan score_plan(int B, int H_q, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse) {
+ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse) {
     ScorePlan pl;
     auto up = [](size_t x) { return (x + 15) & ~(size_t)15; };
     // two passes over the keys
@@ -1244,13 +1256,22 @@ ScorePlan score_plan(int B, int H_q, int sel_group, int max_seqlen, int dtype, i
     const int nf = (max_seqlen + kFusedChunk - 1) / kFusedChunk;
     pl.off_arrive = up((size_t)B * H_q * nf * O * sizeof(float));
     const size_t one_pass = pl.off_arrive + up((size_t)B * H_q * kArriveStride * sizeof(int32_t));
-    const bool can_fuse = CSP_SCORE_FUSED != 0 && dtype == CSP_BF16 && O <= 64 && sel_group == 1;
+    // A workgroup of the one-pass kernel waits for the other chunks of its head.  Workgroups start in
+    // id order and the chunks of the heads of one KV head occupy G * nf consecutive ids, so the ones
+    // waited for are running as long as such a run fits the resident set (512 workgroups on the
+    // whole chip) with room to spare; longer sequences take the two-pass kernels.
+    const int G = H_kv > 0 ? H_q / H_kv : 1;
+    const bool can_fuse = CSP_SCORE_FUSED != 0 && dtype == CSP_BF16 && O <= 64 && (int64_t)G * nf <= 256;
     pl.part_bytes = can_fuse && one_pass > two_pass ? one_pass : two_pass;   // csp_score_lse shares the size
     pl.fused = can_fuse && !have_row_lse;
     pl.chunk_keys = pl.fused ? kFusedChunk : ck;
     pl.n_chunks = pl.fused ? nf : nc;
-    pl.gper = score_heads_per_slice(B, H_q, sel_group, pl.n_chunks);
+    // one pass: every head writes its own array and the heads of a group are added in order
+    pl.gper = pl.fused ? 1 : score_heads_per_slice(B, H_q, sel_group, pl.n_chunks);
     pl.gsplit = (sel_group + pl.gper - 1) / pl.gper;
+    // slice arrays sized for whichever path needs more of them
+    pl.max_gsplit = pl.gsplit;
+    if (can_fuse && sel_group > pl.max_gsplit) pl.max_gsplit = sel_group;
     return pl;
 }
 

@@ -63,6 +63,9 @@ SCORE_CASES = {
     "visual_window": dict(layouts=[[(0, 200), (1, 100), (0, 150), (1, 400)]]),
     "mixed_window": dict(layouts=[[(0, 200), (1, 300), (0, 40), (1, 10), (0, 10), (1, 5)]]),
     "long_multi_chunk": dict(layouts=[[(0, 1000), (1, 5000), (0, 777), (1, 2000), (0, 500)]], H_q=1, H_kv=1),
+    # beyond 256 chunks of 512 keys per KV head the single-read kernel hands over to the two passes
+    "very_long_takes_two_passes": dict(H_q=2, H_kv=2, layouts=[[(0, 3000), (1, 120000), (0, 772), (1, 8000), (0, 100)]],
+                                       budgets=[4096]),
     "ragged_multi_chunk_d64": dict(H_q=3, H_kv=3, D=64, O=32, R=20, n_score=1.0,
                                    layouts=[[(0, 40), (1, 1500), (0, 33)], [(1, 513), (0, 32)], [(0, 32)],
                                             [(0, 3), (1, 1020), (0, 1)]], budgets=[400, 200, 32, 300]),
@@ -95,7 +98,7 @@ def test_score_matches_oracle(gpu, oracle, name):
 
 
 @pytest.mark.parametrize("name", ["bf16_d128_o64", "bf16_d64_o32", "o8_r3", "r_zero", "nscore_1", "ragged_batch", "visual_window",
-                                  "mixed_window", "long_multi_chunk", "ragged_multi_chunk_d64"])
+                                  "mixed_window", "long_multi_chunk", "ragged_multi_chunk_d64", "gqa_group4", "all_heads_one_group"])
 def test_score_single_read_without_waiting(gpu, oracle, name):
     """The single-read kernel with its wait for the other chunks of a head switched off from the
     host: every workgroup computes the statistics of the whole head by itself (the path taken
