@@ -107,15 +107,15 @@ const char* csp_version(void);
  *   modality  device uint8[total_tokens], 0 = text, 1 = visual
  *   score_*   device float [H_sel][total_tokens]
  *   ws        device scratch of csp_score_workspace_bytes(desc) bytes, 16-byte aligned
- *             (softmax statistics per chunk and, on the single-read path, one
- *             arrival counter per head, cleared by the call itself; for a large
+ *             (softmax statistics per chunk, reset by the call itself; for a large
  *             selection group that is summed in several slices, also one partial
  *             score array per slice, added in slice order: the result does not
  *             depend on scheduling).  Two calls that overlap in time (different
  *             streams) need a workspace each.
- * bf16 with O <= 64 and sel_group == 1 reads the keys once (the workgroups of a
- * head exchange their row statistics inside the launch); other shapes read them
- * twice.  Results are the same up to rounding.
+ * bf16 with O <= 64 and at most 131072 keys per sequence (divided by the GQA
+ * group size) reads the keys once: the workgroups of a head exchange their row
+ * statistics inside the launch.  Other shapes read them twice.  Results are the
+ * same up to rounding.
  * Requires O <= L_b and R <= L_b for every sequence (CSP_EINVAL otherwise);
  * O <= 128.
  * ---------------------------------------------------------------------- */

@@ -132,7 +132,6 @@ static int score_common(const csp_desc* d, const void* q_win, const void* k, con
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
     const ScorePlan pl = score_plan(d->B, d->H_q, d->H_kv, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, row_lse != nullptr);
     p.fused = pl.fused ? 1 : 0;
-    p.arrive = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + pl.off_arrive);
     p.spin_ticks = g_score_spin_ticks.load();
     p.chunk_keys = pl.chunk_keys; p.n_chunks = pl.n_chunks;
     p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
@@ -388,7 +387,6 @@ int csp_reprune(const csp_desc* d, const void* q_ring, int32_t ring_start, void*
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
     p.fused = l.plan.fused ? 1 : 0;
-    p.arrive = reinterpret_cast<int32_t*>(wsb + l.off_part + l.plan.off_arrive);
     p.spin_ticks = g_score_spin_ticks.load();
     p.chunk_keys = l.plan.chunk_keys; p.n_chunks = l.plan.n_chunks; p.gper = l.plan.gper; p.gsplit = l.plan.gsplit;
     if (l.plan.gsplit > 1) {

@@ -74,8 +74,8 @@ struct ScoreParams {
     float* score_self;
     float* score_cross;
     float* part;          // two passes: [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units;
-                          // one pass: [B][H_q][n_chunks][O] log-sum-exp of a chunk in log2 units
-    int32_t* arrive;      // one pass: [B][H_q] chunks of the head that have published their statistics
+                          // one pass: [B][H_q][n_chunks][O] log-sum-exp of a chunk in log2 units, NaN = not
+                          // yet published
     int64_t spin_ticks;   // one pass: longest wait for the other chunks, in 10 ns ticks; 0 = do not wait
     int32_t fused;        // 1: one pass over the keys (score_plan decides)
     const float* row_lse; // [B][H_q][O] natural-log normaliser of every window row, supplied by the caller
@@ -194,7 +194,6 @@ struct ScorePlan {
     int chunk_keys, n_chunks, gper, gsplit;
     int max_gsplit;        // slice arrays the workspace holds (covers csp_score and csp_score_lse)
     size_t part_bytes;     // statistics region at the start of the workspace (16-byte multiple)
-    size_t off_arrive;     // one pass: offset of the arrival counters inside that region
 };
 ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse);
 int score_chunk_keys(int B, int H_q, int max_seqlen, int dtype, int D, int O);

@@ -684,14 +684,16 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
 // ---------------------------------------------------------------------------
 // A workgroup owns kFusedChunk keys and keeps their logits against the whole window in its
 // accumulator registers (kFusedTiles tiles of 32 keys per wavefront).  It publishes the
-// log-sum-exp of its chunk for every window row, waits until the other chunks of the same head
-// have done so, and turns its registers into normalised weights: no second walk over the keys.
+// log-sum-exp of its chunk for every window row, reads the ones of the other chunks of the same
+// head, and turns its registers into normalised weights: no second walk over the keys.
 // The exchange uses agent-scope atomic stores and loads (write-through / read-through at the
-// level the XCDs share) and a counter per head; no release fence, which on this part would
-// write back a whole L2.  Workgroups start in the order of their linear id and the chunks of
-// a head have consecutive ids, so the workgroups waited for are already running; the wait is
-// bounded all the same, and a workgroup that gives up computes the row statistics of the whole
-// head by itself (stats_whole_head), so the kernel ends whatever the scheduling.
+// level the XCDs share) and no release fence, which on this part would write back a whole L2.
+// Every statistic is set to NaN before the launch, so a value that reads as a number has been
+// published: entries validate themselves and no ordering between different addresses is
+// needed.  Workgroups start in the order of their linear id and the chunks of a head have
+// consecutive ids, so the workgroups waited for are already running; the wait is bounded all the
+// same, and a workgroup that gives up computes the row statistics of the whole head by itself
+// (stats_whole_head), so the kernel ends whatever the scheduling.
 #ifndef CSP_FUSED_TILES
 #define CSP_FUSED_TILES 4
 #endif
@@ -704,11 +706,8 @@ constexpr int kFusedOccupancy = kFusedTiles <= 3 ? 3 : 2;  // workgroups per com
 #endif
 constexpr bool kFusedQLds = CSP_FUSED_Q_LDS != 0;
 constexpr int kFusedChunk = kWaves * kTile * kFusedTiles;
-// int32 slots between the arrival counters of two heads: each counter is polled by the waiting
-// workgroups of its head, and neighbours in one 256-byte line would load one memory channel
-constexpr int kArriveStride = 64;
 #ifndef CSP_FUSED_POLL_SLEEP
-#define CSP_FUSED_POLL_SLEEP 16
+#define CSP_FUSED_POLL_SLEEP 4
 #endif
 
 // LDS of the one-pass kernel.  The exchange buffers live inside the key tiles, which are dead once
@@ -828,9 +827,11 @@ __device__ __forceinline__ float2 stats_whole_head(const ScoreParams& p, const c
     return out;
 }
 
+// Marks every (head, chunk, row) statistic as not yet published.
 __global__ __launch_bounds__(256) void score_fused_clear_kernel(ScoreParams p) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < p.B * p.H_q) p.arrive[(size_t)i * kArriveStride] = 0;
+    const size_t n = (size_t)p.B * p.H_q * p.n_chunks * p.O;
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p.part[i] = __builtin_nanf("");
 }
 
 template <typename E, int D, int NQB, bool REUSED>
@@ -1005,51 +1006,44 @@ __global__ __launch_bounds__(kThreads, kFusedOccupancy) void score_fused_kernel(
         const float lse_c = l > 0.f ? rowm[tid] + fast_log2(l) : NEG_INF;
         if (tid < O) __hip_atomic_store(p.part + ((size_t)bh * p.n_chunks + chunk) * O + tid, lse_c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (wave == 0) {
-        // the stores above have reached the level the XCDs share before the counter moves
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (lane == 0) {
-            int32_t* const counter = p.arrive + (size_t)bh * kArriveStride;
-            // the returned count is the first look at the counter: the last chunk to arrive never polls
-            int seen = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
-            int ok = p.spin_ticks > 0;
-            if (ok && seen < n_chunks_b) {
-                const uint64_t t_start = wall_clock64();
-                do {
-                    __builtin_amdgcn_s_sleep(CSP_FUSED_POLL_SLEEP);
-                    if (wall_clock64() - t_start > (uint64_t)p.spin_ticks) { ok = 0; break; }
-                    seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                } while (seen < n_chunks_b);
+    // ---- exchange: the log-sum-exps of all chunks of the head.  Every entry was set to NaN before
+    // the launch, so an entry that reads as a number has been published; entries still NaN are read
+    // again.  Thread (row = tid % 64, quarter = tid / 64) takes every fourth chunk, all its loads in
+    // flight at once; then the four quarters are combined.
+    float M = NEG_INF, Ls = 0.f;
+    bool have_all = p.spin_ticks > 0;  // uniform
+    if (have_all) {
+        const uint64_t t_start = wall_clock64();
+        const int row = tid & 63, quarter = tid >> 6;
+        const float* part = p.part + ((size_t)bh * p.n_chunks) * O + (row < O ? row : 0);
+        for (int cb = 0; cb < n_chunks_b && have_all; cb += 4 * 12) {
+            float r[12];
+            for (;;) {
+                bool pending = false;
+#pragma unroll
+                for (int u = 0; u < 12; ++u) {
+                    const int ch = cb + quarter + 4 * u;
+                    r[u] = ch < n_chunks_b ? __hip_atomic_load(part + (size_t)ch * O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : NEG_INF;
+                    pending |= r[u] != r[u];
+                }
+                if (!__syncthreads_or(pending)) break;
+                // bounded: a workgroup that has waited too long stops depending on the others
+                if (__syncthreads_or(tid == 0 && wall_clock64() - t_start > (uint64_t)p.spin_ticks)) { have_all = false; break; }
+                __builtin_amdgcn_s_sleep(CSP_FUSED_POLL_SLEEP);
             }
-            *flag = ok;
+            if (!have_all) break;
+            float Mn = M;
+#pragma unroll
+            for (int u = 0; u < 12; ++u) Mn = fmaxf(Mn, r[u]);
+            const float Mns = Mn == NEG_INF ? 0.f : Mn;
+            Ls *= fast_exp2(M - Mns);
+#pragma unroll
+            for (int u = 0; u < 12; ++u) Ls += fast_exp2(r[u] - Mns);
+            M = Mn;
         }
     }
-    __syncthreads();
-    const bool have_all = *flag != 0;  // uniform
-    asm volatile("" ::: "memory");
-    float M = NEG_INF, Ls = 0.f;
     if (have_all) {
-        // merge of the chunks' log-sum-exps: thread (row = tid % 64, quarter = tid / 64) takes every
-        // fourth chunk, all its loads in flight at once; then the four quarters are combined
-        {
-            const int row = tid & 63, quarter = tid >> 6;
-            const float* part = p.part + ((size_t)bh * p.n_chunks) * O + (row < O ? row : 0);
-            for (int ch0 = quarter; ch0 < n_chunks_b; ch0 += 4 * 12) {
-                float r[12];
-#pragma unroll
-                for (int u = 0; u < 12; ++u)
-                    r[u] = ch0 + 4 * u < n_chunks_b ? __hip_atomic_load(part + (size_t)(ch0 + 4 * u) * O, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : NEG_INF;
-                float Mn = M;
-#pragma unroll
-                for (int u = 0; u < 12; ++u) Mn = fmaxf(Mn, r[u]);
-                const float Mns = Mn == NEG_INF ? 0.f : Mn;
-                Ls *= fast_exp2(M - Mns);
-#pragma unroll
-                for (int u = 0; u < 12; ++u) Ls += fast_exp2(r[u] - Mns);
-                M = Mn;
-            }
-            SM::red_row(smem, quarter)[row] = make_float2(M, Ls);
-        }
+        SM::red_row(smem, tid >> 6)[tid & 63] = make_float2(M, Ls);
         __syncthreads();
         M = NEG_INF; Ls = 0.f;
         if (tid < NQ) {
@@ -1158,7 +1152,8 @@ hipError_t launch_fused(const ScoreParams& p, hipStream_t s) {
         auto k = p.G > 1 ? score_fused_kernel<E, D, NQB, true> : score_fused_kernel<E, D, NQB, false>;
         const int64_t tasks = (int64_t)p.n_chunks * p.H_q * p.B;
         const unsigned grid = (unsigned)((tasks + 8 * p.G - 1) / (8 * p.G) * (8 * p.G));
-        hipLaunchKernelGGL(score_fused_clear_kernel, dim3((unsigned)((p.B * p.H_q + 255) / 256)), dim3(256), 0, s, p);
+        const size_t n_stats = (size_t)p.B * p.H_q * p.n_chunks * p.O;
+        hipLaunchKernelGGL(score_fused_clear_kernel, dim3((unsigned)((n_stats + 255) / 256)), dim3(256), 0, s, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         const size_t smem = FusedSmem<E, D, NQB>::total;
@@ -1252,10 +1247,9 @@ ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, in
     const int ck = score_chunk_keys(B, H_q, max_seqlen, dtype, D, O);
     const int nc = (max_seqlen + ck - 1) / ck;
     const size_t two_pass = up((size_t)B * H_q * nc * O * 2 * sizeof(float));
-    // one pass: a log-sum-exp per (head, chunk, row) and an arrival counter per head
+    // one pass: a log-sum-exp per (head, chunk, row)
     const int nf = (max_seqlen + kFusedChunk - 1) / kFusedChunk;
-    pl.off_arrive = up((size_t)B * H_q * nf * O * sizeof(float));
-    const size_t one_pass = pl.off_arrive + up((size_t)B * H_q * kArriveStride * sizeof(int32_t));
+    const size_t one_pass = up((size_t)B * H_q * nf * O * sizeof(float));
     // A workgroup of the one-pass kernel waits for the other chunks of its head.  Workgroups start in
     // id order and the chunks of the heads of one KV head occupy G * nf consecutive ids, so the ones
     // waited for are running as long as such a run fits the resident set (512 workgroups on the
