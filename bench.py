@@ -163,16 +163,9 @@ def run_pass(cfg, inputs, layers, dec, decode_steps, timer, sample_every=8, stre
         main = torch.cuda.current_stream()
         for s in streams:
             s.wait_stream(main)
-        stagger = os.environ.get("CSP_BENCH_STAGGER", "0") == "1" and len(streams) == 2
-        first_scored = torch.cuda.Event() if stagger else None
         for li, (inp, lay) in enumerate(zip(inputs, layers)):
-            st = streams[li % len(streams)]
-            with torch.cuda.stream(st):
-                if stagger and li == 1:
-                    st.wait_event(first_scored)
+            with torch.cuda.stream(streams[li % len(streams)]):
                 _score(lay, inp)
-                if stagger and li == 0:
-                    first_scored.record(st)
                 lay.select(inp["mod"])
                 lay.compact(inp["k"], inp["v"])
         for s in streams:
