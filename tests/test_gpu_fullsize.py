@@ -267,3 +267,40 @@ def test_f32_d128_window128_large_chunks(gpu, oracle):
         n = int(cnt[b, h, 0])
         assert n == rc["kept"] == 2048
         U.assert_kept_equivalent(idx[b, h, :n], ref_idx, a_s, a_c, mod_h[lo:hi], L, 128, f"f32 b{b} h{h}")
+
+
+def test_7b_16k_two_streams_bit_identical(gpu):
+    """Two layers pruned at the same time on two streams (what bench.py does) against the same two
+    layers pruned one after the other: scores, kept positions and caches must be bit-identical.
+    The single-read score kernel exchanges statistics between workgroups inside a launch; sharing
+    the chip with another stream's kernels changes when its workgroups start, which must change
+    neither the result nor the path taken (a workgroup whose wait ran out would recompute the
+    statistics in another order and differ in the last bit)."""
+    from paper_2412_04652_amd.runner import CspLayer
+    rng = np.random.default_rng(1000)
+    layouts = [W.layout_7b_16k(rng) for _ in range(4)]
+    T = 8192
+    data = []
+    for seed in (0, 1):
+        q, k, v, mod, cu_dev, cu = W.device_qkv(layouts, H_q=32, H_kv=32, D=128, O=64, seed=seed, device=gpu)
+        mk = lambda: CspLayer(dtype="bf16", H_q=32, H_kv=32, D=128, O=64, R=64, cu_seqlens=cu.tolist(),
+                              budgets=[T] * 4, sel_group=1, decode_cap=1, device=gpu)
+        data.append((q, k, v, mod, mk(), mk()))
+    print("[full] two streams vs serial, 2 layers of 7b_16k", flush=True)
+    for q, k, v, mod, serial, _ in data:
+        serial.prune(q, k, v, mod)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(device=gpu) for _ in range(2)]
+    for rep in range(3):
+        for st, (q, k, v, mod, _, conc) in zip(streams, data):
+            st.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(st):
+                conc.prune(q, k, v, mod)
+        for st in streams:
+            torch.cuda.current_stream().wait_stream(st)
+        torch.cuda.synchronize()
+        for li, (q, k, v, mod, serial, conc) in enumerate(data):
+            assert torch.equal(serial.score_self, conc.score_self) and torch.equal(serial.score_cross, conc.score_cross), (rep, li)
+            assert torch.equal(serial.kept_idx, conc.kept_idx) and torch.equal(serial.kept_cnt, conc.kept_cnt), (rep, li)
+            assert torch.equal(serial.k_cache[:, :, :T].view(torch.int16), conc.k_cache[:, :, :T].view(torch.int16)), (rep, li)
+            assert torch.equal(serial.v_cache[:, :, :T].view(torch.int16), conc.v_cache[:, :, :T].view(torch.int16)), (rep, li)
