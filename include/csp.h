@@ -141,7 +141,7 @@ int csp_score_lse(const csp_desc* desc, const void* q_win, const void* k, const 
                   const float* row_lse, float* score_self, float* score_cross,
                   void* ws, size_t ws_bytes, void* stream);
 
-/* Test hook for csp_score's single-read path (bf16, O <= 64, sel_group == 1), in which the
+/* Test hook for the single-read path of csp_score and csp_reprune (bf16, O <= 64), in which the
  * workgroups of a head exchange their softmax statistics inside one launch: the longest time a
  * workgroup waits for the others before it computes the statistics of the whole head by itself,
  * in 10 ns ticks (default 100000 = 1 ms; 0 = never wait, every workgroup takes the self-sufficient

@@ -723,7 +723,7 @@ struct FusedSmem {
     static constexpr int off_rowm = kTiles;                        // float [NQ] chunk maximum of every row
     static constexpr int off_f = off_rowm + NQ * 4;                // float [NQ] 2^(chunk maximum - lse)
     static constexpr int off_wq = off_f + NQ * 4;                  // uint8 [NQ]
-    static constexpr int off_flag = off_wq + NQ;                   // int [2]: all chunks arrived; modalities in the window
+    static constexpr int off_flag = off_wq + NQ;                   // int [2]: [1] = modalities present in the window
     static constexpr int off_q = (off_flag + 8 + 15) & ~15;        // queries in operand order
     static constexpr int total = off_q + QFrags<E, D, NQB, true>::kLdsBytes;
     static_assert(2 * kFusedChunk * 4 <= kTiles && 64 * 8 <= G::TILE_LDS, "exchange buffers must fit in the tiles");
