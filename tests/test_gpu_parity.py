@@ -99,15 +99,17 @@ def test_score_matches_oracle(gpu, oracle, name):
 
 @pytest.mark.parametrize("name", ["bf16_d128_o64", "bf16_d64_o32", "o8_r3", "r_zero", "nscore_1", "ragged_batch", "visual_window",
                                   "mixed_window", "long_multi_chunk", "ragged_multi_chunk_d64", "gqa_group4", "all_heads_one_group"])
-def test_score_single_read_without_waiting(gpu, oracle, name):
-    """The single-read kernel with its wait for the other chunks of a head switched off from the
-    host: every workgroup computes the statistics of the whole head by itself (the path taken
-    when a wait runs out) and the result is the same."""
+@pytest.mark.parametrize("ticks", [0, 30])
+def test_score_single_read_without_waiting(gpu, oracle, name, ticks):
+    """The single-read kernel with its wait for the other chunks of a head cut short from the
+    host.  0: every workgroup computes the statistics of the whole head by itself (the path taken
+    when a wait runs out); 30 ticks (0.3 us): the workgroups that find the other chunks at their
+    first look go on, the rest give up, both paths in one launch.  The result is the same."""
     import paper_2412_04652_amd as P
     U = _util()
     case = _score_case(name, **SCORE_CASES[name])
-    _say(f"[score, no wait] case={name} dtype={case.dtype} D={case.D} O={case.O} R={case.R}")
-    P.csp_debug_set_score_wait(0)
+    _say(f"[score, wait {ticks} ticks] case={name} dtype={case.dtype} D={case.D} O={case.O} R={case.R}")
+    P.csp_debug_set_score_wait(ticks)
     try:
         _check_score(U, oracle, case, name)
     finally:
