@@ -112,7 +112,7 @@ const char* csp_version(void);
  *             score array per slice, added in slice order: the result does not
  *             depend on scheduling).  Two calls that overlap in time (different
  *             streams) need a workspace each.
- * bf16 with O <= 64 and at most 131072 keys per sequence (divided by the GQA
+ * bf16 with O <= 64 and at most 65536 keys per sequence (divided by the GQA
  * group size) reads the keys once: the workgroups of a head exchange their row
  * statistics inside the launch.  Other shapes read them twice.  Results are the
  * same up to rounding.

@@ -1252,10 +1252,11 @@ ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, in
     const size_t one_pass = up((size_t)B * H_q * nf * O * sizeof(float));
     // A workgroup of the one-pass kernel waits for the other chunks of its head.  Workgroups start in
     // id order and the chunks of the heads of one KV head occupy G * nf consecutive ids, so the ones
-    // waited for are running as long as such a run fits the resident set (512 workgroups on the
-    // whole chip) with room to spare; longer sequences take the two-pass kernels.
+    // waited for are running as long as such a run fits the share of the resident set (512
+    // workgroups on the whole chip) that the launch gets, also beside a second launch on another
+    // stream: a quarter of it is allowed; longer sequences take the two-pass kernels.
     const int G = H_kv > 0 ? H_q / H_kv : 1;
-    const bool can_fuse = CSP_SCORE_FUSED != 0 && dtype == CSP_BF16 && O <= 64 && (int64_t)G * nf <= 256;
+    const bool can_fuse = CSP_SCORE_FUSED != 0 && dtype == CSP_BF16 && O <= 64 && (int64_t)G * nf <= 128;
     pl.part_bytes = can_fuse && one_pass > two_pass ? one_pass : two_pass;   // csp_score_lse shares the size
     pl.fused = can_fuse && !have_row_lse;
     pl.chunk_keys = pl.fused ? kFusedChunk : ck;

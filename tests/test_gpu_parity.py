@@ -63,7 +63,7 @@ SCORE_CASES = {
     "visual_window": dict(layouts=[[(0, 200), (1, 100), (0, 150), (1, 400)]]),
     "mixed_window": dict(layouts=[[(0, 200), (1, 300), (0, 40), (1, 10), (0, 10), (1, 5)]]),
     "long_multi_chunk": dict(layouts=[[(0, 1000), (1, 5000), (0, 777), (1, 2000), (0, 500)]], H_q=1, H_kv=1),
-    # beyond 256 chunks of 512 keys per KV head the single-read kernel hands over to the two passes
+    # beyond 128 chunks of 512 keys per KV head the single-read kernel hands over to the two passes
     "very_long_takes_two_passes": dict(H_q=2, H_kv=2, layouts=[[(0, 3000), (1, 120000), (0, 772), (1, 8000), (0, 100)]],
                                        budgets=[4096]),
     "ragged_multi_chunk_d64": dict(H_q=3, H_kv=3, D=64, O=32, R=20, n_score=1.0,
