@@ -93,7 +93,7 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int j = key_index(sb, i);
-            m[i] = j < c.P ? c.mod[j] : 0;
+            m[i] = c.mod[j < c.P ? j : 0];   // every lane loads (a clamped index): no load under a branch
         }
         in_cross = 0u;
 #pragma unroll
@@ -103,10 +103,13 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
                 ka[i] = j < c.P ? __float_as_uint(c.sc_self[j]) : kNone;
                 kb[i] = j < c.P ? __float_as_uint(c.sc_cross[j]) : kNone;
             } else {
-                // the window has one modality: keys sharing it rank in the self region, the rest in cross
+                // the window has one modality: keys sharing it rank in the self region, the rest in cross.
+                // Both scores are requested at once, beside the modality, and one is picked: a load whose
+                // address waits for the modality would add a memory round trip to a latency-bound kernel
+                const int jc = j < c.P ? j : 0;
+                const uint32_t ss = __float_as_uint(c.sc_self[jc]), sx = __float_as_uint(c.sc_cross[jc]);
                 const bool self_key = m[i] ? c.has1 : c.has0;
-                ka[i] = kNone;
-                if (j < c.P) ka[i] = __float_as_uint(self_key ? c.sc_self[j] : c.sc_cross[j]);
+                ka[i] = j < c.P ? (self_key ? ss : sx) : kNone;
                 if (!self_key) in_cross |= 1u << i;
             }
         }
