@@ -49,6 +49,16 @@ def test_workspace_sizes(P):
     d = _desc(P)
     # chunks of 128 keys at this size: 2*8*32 chunks * 64 rows * 2 floats
     assert P.csp_score_workspace_bytes(d) == 2 * 8 * 32 * 64 * 2 * 4
+    # benchmark shape: the single-read path keeps one float per (head, 512-key chunk, row), which is
+    # more than the two-pass statistics (4 chunks of 4096 keys, two floats each)
+    L = 16384
+    big = dict(B=4, H_q=32, H_kv=32, max_seqlen=L, cu_seqlens_host=[0, L, 2 * L, 3 * L, 4 * L], budget_T_host=[L // 2] * 4,
+               k_strides=(128, 4 * L * 128), v_strides=(128, 4 * L * 128))
+    assert P.csp_score_workspace_bytes(_desc(P, **big)) == 4 * 32 * 32 * 64 * 4
+    # all heads in one selection group: one score array pair per head on top of that
+    assert P.csp_score_workspace_bytes(_desc(P, sel_group=32, **big)) == 4 * 32 * 32 * 64 * 4 + 2 * 32 * 4 * L * 4
+    # fp32 keeps the two passes
+    assert P.csp_score_workspace_bytes(_desc(P, dtype="f32", **big)) == 4 * 32 * 4 * 64 * 2 * 4
     assert P.csp_select_workspace_bytes(d) == 0
     n = P.csp_decode_workspace_bytes(d, 2048 + 16)
     assert n % ((128 + 2) * 4 * 2 * 8) == 0 and n > 0

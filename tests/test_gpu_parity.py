@@ -63,6 +63,8 @@ SCORE_CASES = {
     "visual_window": dict(layouts=[[(0, 200), (1, 100), (0, 150), (1, 400)]]),
     "mixed_window": dict(layouts=[[(0, 200), (1, 300), (0, 40), (1, 10), (0, 10), (1, 5)]]),
     "long_multi_chunk": dict(layouts=[[(0, 1000), (1, 5000), (0, 777), (1, 2000), (0, 500)]], H_q=1, H_kv=1),
+    # the longest sequence of the single-read kernel: 128 chunks per head, merged in three rounds of 48
+    "long_128_chunks": dict(H_q=1, H_kv=1, layouts=[[(0, 1000), (1, 60000), (0, 4536)]], budgets=[4096]),
     # beyond 128 chunks of 512 keys per KV head the single-read kernel hands over to the two passes
     "very_long_takes_two_passes": dict(H_q=2, H_kv=2, layouts=[[(0, 3000), (1, 120000), (0, 772), (1, 8000), (0, 100)]],
                                        budgets=[4096]),
@@ -98,7 +100,8 @@ def test_score_matches_oracle(gpu, oracle, name):
 
 
 @pytest.mark.parametrize("name", ["bf16_d128_o64", "bf16_d64_o32", "o8_r3", "r_zero", "nscore_1", "ragged_batch", "visual_window",
-                                  "mixed_window", "long_multi_chunk", "ragged_multi_chunk_d64", "gqa_group4", "all_heads_one_group"])
+                                  "mixed_window", "long_multi_chunk", "long_128_chunks", "ragged_multi_chunk_d64", "gqa_group4",
+                                  "all_heads_one_group"])
 @pytest.mark.parametrize("ticks", [0, 30])
 def test_score_single_read_without_waiting(gpu, oracle, name, ticks):
     """The single-read kernel with its wait for the other chunks of a head cut short from the
