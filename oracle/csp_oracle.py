@@ -126,9 +126,9 @@ def select(a_self, a_cross, mod, O: int, R: int, T: int, cross_ratio: float = 0.
     a_self, a_cross = _d(a_self), _d(a_cross)
     mod = np.ascontiguousarray(mod, dtype=np.uint8)
     L = mod.shape[0]
-    idx = np.full(max(min(T, L), 0) if combine == "union" else L, -1, dtype=np.int32)
-    if idx.size == 0:
-        idx = np.full(1, -1, dtype=np.int32)
+    # room for every key: no reading of the method keeps more, and a wrong count (which the pins
+    # check) must never write past the buffer
+    idx = np.full(max(L, 1), -1, dtype=np.int32)
     cnt = np.zeros(4, dtype=np.int32)
     n = lib().csp_oracle_select(_p(a_self, C.c_double), _p(a_cross, C.c_double), _p(mod, C.c_uint8),
                                 L, int(O), int(R), int(T), float(cross_ratio),

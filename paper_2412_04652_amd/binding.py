@@ -53,6 +53,13 @@ def load_library():
             raise RuntimeError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2412_04652_amd.build` "
                 "(hipcc, gfx950); the HIP library is the only implementation")
+        # The process must hold ONE HIP runtime: the one torch ships, which owns the device memory
+        # and the streams handed to this library.  torch's libraries ask for "libamdhip64.so" and
+        # libcsp.so for the soname "libamdhip64.so.7"; loaded first, libcsp.so pulls in the system
+        # runtime and torch then maps its own copy beside it (two runtimes, two HSA instances; their
+        # exit handlers have aborted finished processes, and a stream of one means nothing to the
+        # other).  With torch's copy already mapped the loader resolves libcsp.so against it.
+        import torch  # noqa: F401
         L = C.CDLL(_LIB_PATH)
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         dp = C.POINTER(_CDesc)

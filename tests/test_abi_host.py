@@ -161,3 +161,15 @@ def test_binding_fails_loudly_without_library(monkeypatch, P):
     monkeypatch.setattr(b, "_LIB_PATH", "/nonexistent/libcsp.so")
     with pytest.raises(RuntimeError):
         b.load_library()
+
+
+def test_one_hip_runtime_in_the_process(P):
+    """libcsp.so must resolve against the HIP runtime torch ships (the owner of the streams and
+    the device memory it is handed), not map the system runtime beside it: two runtimes in one
+    process are what made finished test processes abort in their exit handlers."""
+    import torch  # noqa: F401
+    maps = open("/proc/self/maps").read()
+    hip = set(re.findall(r"(/\S*libamdhip64[^\s]*)", maps))
+    hsa = set(re.findall(r"(/\S*libhsa-runtime64[^\s]*)", maps))
+    assert len(hip) == 1, hip
+    assert len(hsa) == 1, hsa

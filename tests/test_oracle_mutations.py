@@ -89,25 +89,48 @@ def _load_mutant(tmpdir, name, old, new):
     return mod
 
 
-@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
-def test_pins_catch_planted_mistake(tmp_path, name, old, new):
-    sys.path.insert(0, HERE)
-    mutant = _load_mutant(str(tmp_path), name, old, new)
-    failed = []
+def _run_pins(mutant):
+    """Runs the pins against `mutant` until one fails; returns its name (None: all passed)."""
     for fn, kw in _pins():
         try:
             fn(mutant, **kw)
         except BaseException as e:   # assertion, ValueError from a now-invalid call, pytest.fail, ...
             if isinstance(e, (KeyboardInterrupt, SystemExit)):
                 raise
-            failed.append(fn.__name__)
-            break
-    assert failed, f"no pin noticed the planted mistake '{name}'"
+            return fn.__name__
+    return None
+
+
+# A mutant is wrong code on purpose, and wrong C code may also write out of bounds (one key too many
+# overruns the caller's index buffer): every mutant therefore runs in a process of its own, where a
+# crash is one more way of being noticed and cannot corrupt the heap of the test session.
+_EXIT_NOTICED, _EXIT_UNNOTICED = 3, 0
+
+
+def _child(tmpdir, index):
+    name, old, new = MUTATIONS[index]
+    sys.path.insert(0, HERE)
+    sys.path.insert(0, ROOT)
+    failed = _run_pins(_load_mutant(tmpdir, name, old, new))
+    print(f"mutant {name}: {'noticed by ' + failed if failed else 'NOT noticed'}", flush=True)
+    return _EXIT_NOTICED if failed else _EXIT_UNNOTICED
+
+
+@pytest.mark.parametrize("index", range(len(MUTATIONS)), ids=[m[0] for m in MUTATIONS])
+def test_pins_catch_planted_mistake(tmp_path, index):
+    import subprocess
+    res = subprocess.run([sys.executable, os.path.abspath(__file__), str(tmp_path), str(index)],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
+    # exit 3: a pin failed; a signal or any other status: the mutant crashed (noticed as well)
+    assert res.returncode != _EXIT_UNNOTICED, f"no pin noticed the planted mistake '{MUTATIONS[index][0]}'\n{res.stdout}"
 
 
 def test_unmutated_source_passes_the_same_pins(tmp_path):
     sys.path.insert(0, HERE)
     src = open(os.path.join(ROOT, "oracle", "csp_oracle.c")).read()
     clean = _load_mutant(str(tmp_path), "clean", src[:40], src[:40])
-    for fn, kw in _pins():
-        fn(clean, **kw)
+    assert _run_pins(clean) is None
+
+
+if __name__ == "__main__":
+    sys.exit(_child(sys.argv[1], int(sys.argv[2])))
