@@ -214,6 +214,27 @@ int csp_decode_attn(const csp_desc* desc, const void* q, const void* k_cache, co
                     void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
+ * csp_decode_attn_static — csp_decode_attn for callers that cannot allocate
+ * device memory and so cannot bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and the
+ * same result (bit for bit: the same kernels run), without ws / ws_bytes: the
+ * split-KV partials go to a device array that is part of the library's code
+ * object (csp_static_scratch_bytes() = 2 MiB per GPU, held until the process
+ * ends).  The call allocates and frees nothing; the first call on a device
+ * looks up the array's address there.
+ *  - csp_decode_workspace_bytes(desc, max_kv_len) > csp_static_scratch_bytes()
+ *    is CSP_EWORKSPACE (nothing is launched): use csp_decode_attn.
+ *  - Every call on a GPU shares that GPU's array: two calls that overlap in
+ *    time on one GPU (different streams) race; calls on one stream are safe.
+ *    Nothing has to start at zero (the first kernel writes every partial the
+ *    second one reads).
+ * ---------------------------------------------------------------------- */
+size_t csp_static_scratch_bytes(void);
+int csp_decode_attn_static(const csp_desc* desc, const void* q, const void* k_cache, const void* v_cache,
+                           int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                           const int32_t* kv_len, int32_t max_kv_len, float* out, void* stream);
+
+/* ------------------------------------------------------------------------
  * csp_decode_step — csp_append_kv followed by csp_decode_attn in one call (one
  * kernel launch fewer per decode step): the new token's key and value (device
  * [B][H_kv][D]) are appended at row kv_len[b][h] of the pruned cache, attended

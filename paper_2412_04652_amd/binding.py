@@ -16,7 +16,7 @@ EXPORTED_SYMBOLS = [
     "csp_score_workspace_bytes", "csp_score", "csp_score_lse",
     "csp_select_workspace_bytes", "csp_select",
     "csp_compact",
-    "csp_decode_workspace_bytes", "csp_decode_attn", "csp_decode_step", "csp_decode_step_phase",
+    "csp_decode_workspace_bytes", "csp_decode_attn", "csp_static_scratch_bytes", "csp_decode_attn_static", "csp_decode_step", "csp_decode_step_phase",
     "csp_append_kv",
     "csp_gather_modality", "csp_window_push", "csp_decode_step_window", "csp_reprune_workspace_bytes", "csp_reprune",
 ]
@@ -74,6 +74,8 @@ def load_library():
         L.csp_select.argtypes = [dp, vp, vp, vp, vp, i32, vp, vp, sz, vp]; L.csp_select.restype = C.c_int
         L.csp_compact.argtypes = [dp, vp, vp, vp, i32, vp, vp, vp, i64, i64, i64, vp, vp]; L.csp_compact.restype = C.c_int
         L.csp_decode_attn.argtypes = [dp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp, sz, vp]; L.csp_decode_attn.restype = C.c_int
+        L.csp_static_scratch_bytes.argtypes = []; L.csp_static_scratch_bytes.restype = sz
+        L.csp_decode_attn_static.argtypes = [dp, vp, vp, vp, i64, i64, i64, vp, i32, vp, vp]; L.csp_decode_attn_static.restype = C.c_int
         L.csp_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]; L.csp_decode_step.restype = C.c_int
         L.csp_decode_step_phase.argtypes = [dp, i32, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, sz, vp]; L.csp_decode_step_phase.restype = C.c_int
         L.csp_append_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]; L.csp_append_kv.restype = C.c_int
@@ -199,6 +201,17 @@ def csp_decode_attn(desc: Desc, q, k_cache, v_cache, cache_strides, kv_len, max_
     _check(load_library().csp_decode_attn(desc.ref(), _ptr(q), _ptr(k_cache), _ptr(v_cache), int(cache_strides[0]),
                                           int(cache_strides[1]), int(cache_strides[2]), _ptr(kv_len), int(max_kv_len),
                                           _ptr(out), _ptr(ws), _nbytes(ws), _stream(stream)), "csp_decode_attn")
+
+
+def csp_static_scratch_bytes() -> int:
+    return int(load_library().csp_static_scratch_bytes())
+
+
+def csp_decode_attn_static(desc: Desc, q, k_cache, v_cache, cache_strides, kv_len, max_kv_len: int, out, stream=None) -> None:
+    """csp_decode_attn without a workspace argument: the library's own device scratch array is used"""
+    _check(load_library().csp_decode_attn_static(desc.ref(), _ptr(q), _ptr(k_cache), _ptr(v_cache), int(cache_strides[0]),
+                                                 int(cache_strides[1]), int(cache_strides[2]), _ptr(kv_len), int(max_kv_len),
+                                                 _ptr(out), _stream(stream)), "csp_decode_attn_static")
 
 
 def csp_append_kv(desc: Desc, k_new, v_new, k_cache, v_cache, cache_strides, cache_cap: int, kv_len,

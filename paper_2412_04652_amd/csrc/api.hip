@@ -4,6 +4,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "csp_internal.h"
 
@@ -201,6 +202,32 @@ int csp_compact(const csp_desc* d, const void* k, const void* v, const int32_t* 
     return launch_compact(p, c.row_bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
 }
 
+// ---- csp_decode_attn_static: the split-KV partials live in a device array of the library ------
+// Host code never passes the array's NAME to a kernel (in host code it is only a stand-in for the
+// symbol): its device address is looked up once per device and kept.
+#define CSP_STATIC_SCRATCH_BYTES (2u << 20)
+static __device__ __align__(256) unsigned char scratch[CSP_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device (each device holds its own copy).
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CSP_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return CSP_EHIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CSP_OK;
+}
+}  // namespace
+
 size_t csp_decode_workspace_bytes(const csp_desc* d, int32_t max_kv_len) {
     if (!d || d->B <= 0 || d->H_q <= 0 || d->H_kv <= 0 || max_kv_len <= 0) return 0;
     const int ns = decode_num_splits(d->B, d->H_kv, max_kv_len);
@@ -211,7 +238,7 @@ static int decode_common(const csp_desc* d, const void* q, const void* k_new, co
                          void* k_cache, void* v_cache, int64_t cache_stride_b, int64_t cache_stride_head,
                          int64_t cache_stride_tok, int32_t cache_cap, int32_t* kv_len, int32_t max_kv_len,
                          float* out, void* ws, size_t ws_bytes, void* stream, int phases = 3,
-                         void* q_ring = nullptr, int32_t ring_slot = 0) {
+                         void* q_ring = nullptr, int32_t ring_slot = 0, bool static_ws = false) {
     Checked c;
     int rc = check_desc(d, false, &c);
     if (rc != CSP_OK) return rc;
@@ -222,6 +249,12 @@ static int decode_common(const csp_desc* d, const void* q, const void* k_new, co
     if ((rc = check_kv_strides(cache_stride_tok, cache_stride_head, d->D, c.EB)) != CSP_OK) return rc;
     if (cache_stride_b < 0 || (cache_stride_b * c.EB) % 16 != 0) return CSP_EINVAL;
     const size_t need = csp_decode_workspace_bytes(d, max_kv_len);
+    if (static_ws) {
+        // the library's own scratch array; looked up only now, when every argument has been checked
+        if (need > CSP_STATIC_SCRATCH_BYTES) return CSP_EWORKSPACE;
+        if ((rc = static_scratch(&ws)) != CSP_OK) return rc;
+        ws_bytes = CSP_STATIC_SCRATCH_BYTES;
+    }
     if (!ws || ws_bytes < need || !aligned16(ws)) return CSP_EWORKSPACE;
     DecodeParams p;
     std::memset(&p, 0, sizeof(p));
@@ -247,6 +280,19 @@ int csp_decode_attn(const csp_desc* d, const void* q, const void* k_cache, const
     return decode_common(d, q, nullptr, nullptr, const_cast<void*>(k_cache), const_cast<void*>(v_cache), cache_stride_b,
                          cache_stride_head, cache_stride_tok, 0, const_cast<int32_t*>(kv_len), max_kv_len, out, ws,
                          ws_bytes, stream);
+}
+
+size_t csp_static_scratch_bytes(void) { return CSP_STATIC_SCRATCH_BYTES; }
+
+int csp_decode_attn_static(const csp_desc* d, const void* q, const void* k_cache, const void* v_cache,
+                           int64_t cache_stride_b, int64_t cache_stride_head, int64_t cache_stride_tok,
+                           const int32_t* kv_len, int32_t max_kv_len, float* out, void* stream) {
+    // sizes beyond the library's own scratch are refused first: use csp_decode_attn for those
+    if (d && max_kv_len > 0 && csp_decode_workspace_bytes(d, max_kv_len) > CSP_STATIC_SCRATCH_BYTES) return CSP_EWORKSPACE;
+    // the partials are written by the first kernel before the second reads them: nothing to clear
+    return decode_common(d, q, nullptr, nullptr, const_cast<void*>(k_cache), const_cast<void*>(v_cache), cache_stride_b,
+                         cache_stride_head, cache_stride_tok, 0, const_cast<int32_t*>(kv_len), max_kv_len, out, nullptr,
+                         0, stream, 3, nullptr, 0, true);
 }
 
 int csp_decode_step(const csp_desc* d, const void* q, const void* k_new, const void* v_new, void* k_cache,
