@@ -83,6 +83,10 @@ typedef struct csp_desc {
     const int32_t* budget_T;        /* device int32[B], same values */
     int64_t k_stride_tok, k_stride_head; /* elements */
     int64_t v_stride_tok, v_stride_head; /* elements */
+    int32_t score_wait_us; /* csp_score / csp_reprune, single-read kernel: the longest time a workgroup waits for
+                              the softmax statistics of the other chunks of its head before it recomputes them
+                              itself, in microseconds; 0 = default (1000); negative = never wait (every task takes
+                              the self-sufficient path: a test setting).  The result does not depend on it. */
 } csp_desc;
 
 /* Human-readable name of an error code (static string). */
@@ -107,15 +111,22 @@ const char* csp_version(void);
  *   modality  device uint8[total_tokens], 0 = text, 1 = visual
  *   score_*   device float [H_sel][total_tokens]
  *   ws        device scratch of csp_score_workspace_bytes(desc) bytes, 16-byte aligned
- *             (softmax statistics per chunk, reset by the call itself; for a large
- *             selection group that is summed in several slices, also one partial
- *             score array per slice, added in slice order: the result does not
- *             depend on scheduling).  Two calls that overlap in time (different
- *             streams) need a workspace each.
- * bf16 with O <= 64 and at most 65536 keys per sequence (divided by the GQA
- * group size) reads the keys once: the workgroups of a head exchange their row
- * statistics inside the launch.  Other shapes read them twice.  Results are the
- * same up to rounding.
+ *             (counters, softmax statistics per chunk, reset by the call itself; for a
+ *             selection group that is summed in several slices, also one partial score
+ *             array per slice, added in slice order: the result does not depend on
+ *             scheduling).  Two calls that overlap in time (different streams) need a
+ *             workspace each.  The first 16 bytes are int32 counters the call writes:
+ *             [0] = tasks of the single-read kernel whose wait ran out (see below; 0
+ *             unless the GPU was shared or score_wait_us was set very low).
+ * bf16 with O <= 128 and G * ceil(O/64) * ceil(max_seqlen/512) <= 256 (G = H_q/H_kv:
+ * 131072 keys per sequence for G = 1, O <= 64) reads the keys ONCE: a resident set of
+ * one workgroup per compute unit walks 512-key chunks, keeps a chunk's logits in
+ * registers, and the workgroups of a head exchange the chunks' log-sum-exps inside the
+ * launch, one pipeline step behind the logits.  A workgroup whose bounded wait for the
+ * others runs out (score_wait_us) recomputes the statistics of the head's chunks by
+ * itself with the same code, in the same order: the scores are bit-identical either
+ * way.  Other shapes (fp32, longer sequences) read the keys twice; results are the same
+ * up to rounding.
  * Requires O <= L_b and R <= L_b for every sequence (CSP_EINVAL otherwise);
  * O <= 128.
  * ---------------------------------------------------------------------- */
@@ -140,13 +151,6 @@ int csp_score(const csp_desc* desc, const void* q_win, const void* k, const uint
 int csp_score_lse(const csp_desc* desc, const void* q_win, const void* k, const uint8_t* modality,
                   const float* row_lse, float* score_self, float* score_cross,
                   void* ws, size_t ws_bytes, void* stream);
-
-/* Test hook for the single-read path of csp_score and csp_reprune (bf16, O <= 64), in which the
- * workgroups of a head exchange their softmax statistics inside one launch: the longest time a
- * workgroup waits for the others before it computes the statistics of the whole head by itself,
- * in 10 ns ticks (default 100000 = 1 ms; 0 = never wait, every workgroup takes the self-sufficient
- * path).  Results do not depend on the value beyond rounding.  Process-wide; host-side only. */
-void csp_debug_set_score_wait(int64_t ticks);
 
 /* ------------------------------------------------------------------------
  * csp_select — Eq. "top-K" per region, the mask combination (read as the

@@ -12,7 +12,7 @@ _lib = None
 CSP_BF16, CSP_F32 = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "csp_strerror", "csp_version", "csp_debug_set_score_wait",
+    "csp_strerror", "csp_version",
     "csp_score_workspace_bytes", "csp_score", "csp_score_lse",
     "csp_select_workspace_bytes", "csp_select",
     "csp_compact",
@@ -38,6 +38,7 @@ class _CDesc(C.Structure):
         ("cu_seqlens", C.c_void_p), ("budget_T", C.c_void_p),
         ("k_stride_tok", C.c_int64), ("k_stride_head", C.c_int64),
         ("v_stride_tok", C.c_int64), ("v_stride_head", C.c_int64),
+        ("score_wait_us", C.c_int32),
     ]
 
 
@@ -65,7 +66,6 @@ def load_library():
         dp = C.POINTER(_CDesc)
         L.csp_strerror.argtypes = [C.c_int]; L.csp_strerror.restype = C.c_char_p
         L.csp_version.argtypes = []; L.csp_version.restype = C.c_char_p
-        L.csp_debug_set_score_wait.argtypes = [i64]; L.csp_debug_set_score_wait.restype = None
         L.csp_score_workspace_bytes.argtypes = [dp]; L.csp_score_workspace_bytes.restype = sz
         L.csp_select_workspace_bytes.argtypes = [dp]; L.csp_select_workspace_bytes.restype = sz
         L.csp_decode_workspace_bytes.argtypes = [dp, i32]; L.csp_decode_workspace_bytes.restype = sz
@@ -98,12 +98,6 @@ def csp_version() -> str:
     return load_library().csp_version().decode()
 
 
-def csp_debug_set_score_wait(ticks: int) -> None:
-    """Test hook: longest wait (10 ns ticks) of the single-read score kernel for the other
-    chunks of a head; 0 makes every workgroup take its self-sufficient path."""
-    load_library().csp_debug_set_score_wait(C.c_int64(int(ticks)))
-
-
 class Desc:
     """Python mirror of `csp_desc`.  Host arrays are kept alive by this object;
     device arrays are torch int32 tensors (or raw pointers for validation tests)."""
@@ -112,7 +106,7 @@ class Desc:
                  window_O: int, recent_R: int, max_seqlen: int, cu_seqlens_host: Optional[Sequence[int]],
                  budget_T_host: Optional[Sequence[int]], cu_seqlens=None, budget_T=None,
                  k_strides=(0, 0), v_strides=(0, 0), causal: bool = True, n_score: float = 0.0,
-                 n_decode: float = 1.0, cross_ratio: float = 0.5):
+                 n_decode: float = 1.0, cross_ratio: float = 0.5, score_wait_us: int = 0):
         self._cu_host = (C.c_int32 * (B + 1))(*[int(x) for x in cu_seqlens_host]) if cu_seqlens_host is not None else None
         self._bt_host = (C.c_int32 * B)(*[int(x) for x in budget_T_host]) if budget_T_host is not None else None
         self._keep = (cu_seqlens, budget_T)
@@ -127,6 +121,7 @@ class Desc:
         c.budget_T = _ptr(budget_T)
         c.k_stride_tok, c.k_stride_head = int(k_strides[0]), int(k_strides[1])
         c.v_stride_tok, c.v_stride_head = int(v_strides[0]), int(v_strides[1])
+        c.score_wait_us = int(score_wait_us)
         self.c = c
 
     def ref(self):

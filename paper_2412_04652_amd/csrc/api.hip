@@ -1,7 +1,6 @@
 // C ABI of libcsp: host-side validation and marshalling (see include/csp.h for
 // the contract of every entry point).  Nothing here touches the GPU until the
 // arguments have been checked.
-#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -74,6 +73,16 @@ int check_budgets(const csp_desc* d, int kept_cap) {
 
 const double kLog2e = 1.4426950408889634;
 
+// plan -> launch parameters; slices: first byte of the per-slice score arrays
+void set_score_plan(ScoreParams& p, const ScorePlan& pl, const csp_desc* d, char* slices) {
+    p.single = pl.single ? 1 : 0;
+    p.single_chunks = pl.single_chunks; p.vsplit = pl.vsplit;
+    p.chunk_keys = pl.chunk_keys; p.n_chunks = pl.n_chunks; p.gper = pl.gper; p.gsplit = pl.gsplit;
+    p.slice_base = pl.max_gsplit > 1 ? reinterpret_cast<float*>(slices) : nullptr;
+    // longest wait of a single-read workgroup for the other chunks of its head, in 10 ns ticks
+    p.spin_ticks = d->score_wait_us < 0 ? 0 : (d->score_wait_us == 0 ? 100000 : (int64_t)d->score_wait_us * 100);
+}
+
 }  // namespace
 
 extern "C" {
@@ -91,10 +100,6 @@ const char* csp_strerror(int code) {
 
 const char* csp_version(void) { return "csp-gfx950 0.1"; }
 
-// longest wait of a one-pass score workgroup for the other chunks of its head (10 ns ticks)
-static std::atomic<int64_t> g_score_spin_ticks{100000};
-
-void csp_debug_set_score_wait(int64_t ticks) { g_score_spin_ticks.store(ticks < 0 ? 0 : ticks); }
 
 size_t csp_score_workspace_bytes(const csp_desc* d) {
     if (!d || d->B <= 0 || d->H_q <= 0 || d->max_seqlen <= 0 || d->window_O <= 0) return 0;
@@ -125,22 +130,16 @@ static int score_common(const csp_desc* d, const void* q_win, const void* k, con
     std::memset(&p, 0, sizeof(p));
     p.q_win = q_win; p.k = k; p.modality = modality;
     p.score_self = score_self; p.score_cross = score_cross;
-    p.part = static_cast<float*>(ws);
+    p.counters = static_cast<int32_t*>(ws);
+    p.part = reinterpret_cast<float*>(static_cast<char*>(ws) + 16);
     p.row_lse = row_lse;
     p.view.cu = d->cu_seqlens; p.view.H_kv = d->H_kv; p.view.H_sel = c.H_sel; p.view.total_tokens = c.total_tokens;
     p.score_elems = (int64_t)c.H_sel * c.total_tokens;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
     const ScorePlan pl = score_plan(d->B, d->H_q, d->H_kv, d->sel_group, d->max_seqlen, d->dtype, d->D, d->window_O, row_lse != nullptr);
-    p.fused = pl.fused ? 1 : 0;
-    p.spin_ticks = g_score_spin_ticks.load();
-    p.chunk_keys = pl.chunk_keys; p.n_chunks = pl.n_chunks;
+    set_score_plan(p, pl, d, static_cast<char*>(ws) + pl.part_bytes);
     p.k_stride_tok = d->k_stride_tok; p.k_stride_head = d->k_stride_head;
-    p.gper = pl.gper; p.gsplit = pl.gsplit;
-    if (p.gsplit > 1) {
-        p.slice_self = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.part_bytes);
-        p.slice_cross = p.slice_self + (size_t)p.gsplit * (d->H_q / d->sel_group) * c.total_tokens;
-    }
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
     p.n_score = (float)d->n_score;
     return launch_score(p, d->dtype, d->D, d->max_seqlen, static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
@@ -427,18 +426,13 @@ int csp_reprune(const csp_desc* d, const void* q_ring, int32_t ring_start, void*
     std::memset(&p, 0, sizeof(p));
     p.q_win = wsb; p.k = k_cache; p.modality = mod_cache;
     p.score_self = score_self; p.score_cross = score_cross;
-    p.part = reinterpret_cast<float*>(wsb + l.off_part);
+    p.counters = reinterpret_cast<int32_t*>(wsb + l.off_part);
+    p.part = reinterpret_cast<float*>(wsb + l.off_part + 16);
     p.view = view;
     p.score_elems = (int64_t)d->B * c.H_sel * cache_cap;
     p.B = d->B; p.H_q = d->H_q; p.G = c.G; p.sel_group = d->sel_group;
     p.O = d->window_O; p.R = d->recent_R; p.causal = d->causal ? 1 : 0;
-    p.fused = l.plan.fused ? 1 : 0;
-    p.spin_ticks = g_score_spin_ticks.load();
-    p.chunk_keys = l.plan.chunk_keys; p.n_chunks = l.plan.n_chunks; p.gper = l.plan.gper; p.gsplit = l.plan.gsplit;
-    if (l.plan.gsplit > 1) {
-        p.slice_self = reinterpret_cast<float*>(wsb + l.off_slices);
-        p.slice_cross = p.slice_self + (size_t)l.plan.gsplit * p.score_elems;
-    }
+    set_score_plan(p, l.plan, d, wsb + l.off_slices);
     p.k_stride_tok = cache_stride_tok; p.k_stride_head = cache_stride_head;
     p.scale_log2 = (float)(kLog2e / std::sqrt((double)d->D));
     p.n_score = (float)d->n_score;

@@ -67,17 +67,39 @@ __device__ __forceinline__ int64_t view_key0(const SeqView& v, int b, int64_t k_
 }
 
 // ---- launch parameter blocks ------------------------------------------------
+// a record of the single-read score kernel's task table (see score_single.hip)
+struct alignas(16) PipeRec {
+    int32_t valid;         // 0: nothing to compute (the addresses below still point at readable memory)
+    int32_t L;             // keys of the sequence, at least 1
+    int32_t c0;            // first key of the chunk
+    int32_t rows;          // window rows of the part
+    int32_t pos0;          // absolute position of the part's window row 0
+    int32_t spare;
+    const char* kbase;     // key row 0 of the sequence, this KV head
+    const char* qpart;     // query row 0 of the part
+    const uint8_t* mod;    // modality of key 0 of the sequence
+    float* stat;           // statistics of the head part: chunk 0, row 0
+    float* out_self;       // self score of key 0 in the array this task writes (cross: + ScoreParams::cross_delta)
+};
 struct ScoreParams {
     const void* q_win;
     const void* k;
     const uint8_t* modality;
     float* score_self;
     float* score_cross;
+    int32_t* counters;    // int32[4] at the start of the workspace: [0] = tasks of the single-read kernel whose wait
+                          // for the other chunks ran out (statistics recomputed by the workgroup itself)
     float* part;          // two passes: [B][H_q][n_chunks][O][2] partial (max, sum) in log2 units;
-                          // one pass: [B][H_q][n_chunks][O] log-sum-exp of a chunk in log2 units, NaN = not
-                          // yet published
-    int64_t spin_ticks;   // one pass: longest wait for the other chunks, in 10 ns ticks; 0 = do not wait
-    int32_t fused;        // 1: one pass over the keys (score_plan decides)
+                          // single read: [B][H_q][vsplit][n_chunks][64] log-sum-exp of a chunk in log2 units,
+                          // NaN = not yet published
+    int64_t spin_ticks;   // single read: longest wait for the other chunks, in 10 ns ticks; 0 = do not wait
+    int32_t single;       // 1: one read of the keys (score_plan decides)
+    int32_t single_chunks, vsplit;  // single read: 512-key chunks per sequence; parts of <= 64 window rows
+    int32_t n_tasks, n_lin, n_iters;  // single read: tasks, padded task ids, pipeline steps (filled in by the launcher)
+    PipeRec* table;            // single read: task table in the workspace, n_lin + 1 records (filled in by the launcher)
+    int64_t cross_delta;              // single read: elements from the self score array (or slices) to the cross one
+    int32_t D;                        // single read: head dimension
+    float* slice_base;    // first of the per-slice score arrays in the workspace (slice_self/slice_cross are derived)
     const float* row_lse; // [B][H_q][O] natural-log normaliser of every window row, supplied by the caller
                           // (then the statistics pass is skipped and `part` is not used); nullptr otherwise
     float* slice_self;    // [gsplit][score_elems] per-slice sums of a split selection group (gsplit > 1)
@@ -190,11 +212,16 @@ hipError_t launch_window_unroll(const WindowParams& p, hipStream_t s);
 
 // host-side sizing rules shared by the *_workspace_bytes functions and the launchers
 struct ScorePlan {
-    bool fused;            // statistics and column sums from one read of the keys
-    int chunk_keys, n_chunks, gper, gsplit;
-    int max_gsplit;        // slice arrays the workspace holds (covers csp_score and csp_score_lse)
-    size_t part_bytes;     // statistics region at the start of the workspace (16-byte multiple)
+    int chunk_keys, n_chunks, gper, gsplit;   // two passes over the keys
+    bool single;           // statistics and column sums from one read of the keys
+    int single_chunks, vsplit, single_gsplit; // ... its 512-key chunks, window parts and slice arrays
+    int max_gsplit;        // slice arrays the workspace holds (covers both paths and csp_score_lse)
+    size_t part_bytes;     // counters + statistics region at the start of the workspace (16-byte multiple)
 };
+constexpr int kScoreSingleChunk = 512;      // keys per task of the single-read kernel
+constexpr int kScoreSingleRecBytes = 64;    // one task-table record
+constexpr int kScoreSingleMaxIters = 2048;  // pipeline steps one workgroup may run
+hipError_t launch_score_single(ScoreParams& p, int D, hipStream_t s);
 ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, int dtype, int D, int O, bool have_row_lse);
 int score_chunk_keys(int B, int H_q, int max_seqlen, int dtype, int D, int O);
 // heads of a selection group that one workgroup of the column-sum pass sums itself

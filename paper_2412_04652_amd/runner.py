@@ -25,7 +25,7 @@ class CspLayer:
                  cu_seqlens: Sequence[int], budgets: Sequence[int], sel_group: int = 1,
                  cross_ratio: float = 0.5, n_score: float = 0.0, n_decode: float = 1.0,
                  decode_cap: int = 0, device="cuda:0", k_strides=None, v_strides=None, causal: bool = True,
-                 reprune: bool = False):
+                 reprune: bool = False, score_wait_us: int = 0):
         self.device = torch.device(device)
         self.dtype, self.H_q, self.H_kv, self.D, self.O, self.R = dtype, H_q, H_kv, D, O, R
         self.B = len(budgets)
@@ -47,7 +47,7 @@ class CspLayer:
                             recent_R=R, max_seqlen=self.max_seqlen, cu_seqlens_host=self.cu_host,
                             budget_T_host=self.budgets, cu_seqlens=self.cu, budget_T=self.bt,
                             k_strides=ks, v_strides=vs, causal=causal, n_score=n_score, n_decode=n_decode,
-                            cross_ratio=cross_ratio)
+                            cross_ratio=cross_ratio, score_wait_us=score_wait_us)
         self.score_self = torch.empty((self.H_sel, self.total), dtype=torch.float32, device=dev)
         self.score_cross = torch.empty((self.H_sel, self.total), dtype=torch.float32, device=dev)
         self.ws_score = torch.empty(max(B_.csp_score_workspace_bytes(self.desc), 16), dtype=torch.uint8, device=dev)
@@ -78,6 +78,10 @@ class CspLayer:
     # -- the four calls of the path, in order ---------------------------------
     def score(self, q_win, k, modality, stream=None):
         B_.csp_score(self.desc, q_win, k, modality, self.score_self, self.score_cross, self.ws_score, stream)
+
+    def score_fallbacks(self) -> int:
+        """tasks of the last csp_score call whose wait for the other chunks ran out (first counter of the workspace)"""
+        return int(self.ws_score[:4].view(torch.int32).item())
 
     def score_lse(self, q_win, k, modality, row_lse, stream=None):
         """score with the window rows' log-sum-exp supplied (the keys are read once)"""

@@ -26,7 +26,7 @@ def from_dev_bits(t: torch.Tensor, dtype: str) -> np.ndarray:
 
 
 class DeviceCase:
-    def __init__(self, case, decode_cap: int = 0, device="cuda:0", reprune: bool = False):
+    def __init__(self, case, decode_cap: int = 0, device="cuda:0", reprune: bool = False, score_wait_us: int = 0):
         self.case = case
         self.q_win = to_dev(case.q_win, case.dtype, device)
         self.k = to_dev(case.k, case.dtype, device)
@@ -35,7 +35,8 @@ class DeviceCase:
         self.layer = CspLayer(dtype=case.dtype, H_q=case.H_q, H_kv=case.H_kv, D=case.D, O=case.O, R=case.R,
                               cu_seqlens=case.cu_seqlens.tolist(), budgets=case.budget_T.tolist(),
                               sel_group=case.sel_group, cross_ratio=case.cross_ratio, n_score=case.n_score,
-                              n_decode=case.n_decode, decode_cap=decode_cap, device=device, reprune=reprune)
+                              n_decode=case.n_decode, decode_cap=decode_cap, device=device, reprune=reprune,
+                              score_wait_us=score_wait_us)
 
 
 def assert_scores_close(gpu: np.ndarray, ref: np.ndarray, what: str = "") -> None:

@@ -47,18 +47,24 @@ def _desc(P, **kw):
 
 def test_workspace_sizes(P):
     d = _desc(P)
-    # chunks of 128 keys at this size: 2*8*32 chunks * 64 rows * 2 floats
-    assert P.csp_score_workspace_bytes(d) == 2 * 8 * 32 * 64 * 2 * 4
-    # benchmark shape: the single-read path keeps one float per (head, 512-key chunk, row), which is
-    # more than the two-pass statistics (4 chunks of 4096 keys, two floats each)
+    # 16 bytes of counters, then the statistics of whichever path needs more: two passes with chunks of
+    # 128 keys at this size (2*8*32 chunks * 64 rows * 2 floats) against one float per (head, 512-key
+    # chunk, row) of the single-read kernel
+    assert P.csp_score_workspace_bytes(d) == 16 + 2 * 8 * 32 * 64 * 2 * 4
+    # benchmark shape: the single-read statistics (32 chunks of 512 keys) and its task table (a 64-byte
+    # record per (sequence, head, window part, chunk), and one more) are more than the two-pass
+    # statistics (4 chunks of 4096 keys, two floats each)
     L = 16384
     big = dict(B=4, H_q=32, H_kv=32, max_seqlen=L, cu_seqlens_host=[0, L, 2 * L, 3 * L, 4 * L], budget_T_host=[L // 2] * 4,
                k_strides=(128, 4 * L * 128), v_strides=(128, 4 * L * 128))
-    assert P.csp_score_workspace_bytes(_desc(P, **big)) == 4 * 32 * 32 * 64 * 4
+    table = (4 * 32 * 32 + 1) * 64
+    assert P.csp_score_workspace_bytes(_desc(P, **big)) == 16 + 4 * 32 * 32 * 64 * 4 + table
     # all heads in one selection group: one score array pair per head on top of that
-    assert P.csp_score_workspace_bytes(_desc(P, sel_group=32, **big)) == 4 * 32 * 32 * 64 * 4 + 2 * 32 * 4 * L * 4
+    assert P.csp_score_workspace_bytes(_desc(P, sel_group=32, **big)) == 16 + 4 * 32 * 32 * 64 * 4 + table + 2 * 32 * 4 * L * 4
+    # a window of 128 rows is scored in two parts of 64: statistics and score arrays per part
+    assert P.csp_score_workspace_bytes(_desc(P, window_O=128, recent_R=128, **big)) == 16 + 4 * 32 * 2 * 32 * 64 * 4 + (4 * 32 * 2 * 32 + 1) * 64 + 2 * 2 * 32 * 4 * L * 4
     # fp32 keeps the two passes
-    assert P.csp_score_workspace_bytes(_desc(P, dtype="f32", **big)) == 4 * 32 * 4 * 64 * 2 * 4
+    assert P.csp_score_workspace_bytes(_desc(P, dtype="f32", **big)) == 16 + 4 * 32 * 4 * 64 * 2 * 4
     assert P.csp_select_workspace_bytes(d) == 0
     n = P.csp_decode_workspace_bytes(d, 2048 + 16)
     assert n % ((128 + 2) * 4 * 2 * 8) == 0 and n > 0
@@ -128,9 +134,9 @@ def test_reprune_validation(P):
     cap = 2048 + 64
     sb, sh, st = 8 * cap * 128, cap * 128, 128
     ws = P.csp_reprune_workspace_bytes(d, cap)
-    # ordered window (2*8*64 rows of 256 bytes) + softmax statistics per chunk; no slices for sel_group 1
+    # ordered window (2*8*64 rows of 256 bytes) + counters + softmax statistics per chunk; no slices for sel_group 1
     n_chunks = -(-cap // 128)
-    assert ws == 2 * 8 * 64 * 256 + 2 * 8 * n_chunks * 64 * 2 * 4
+    assert ws == 2 * 8 * 64 * 256 + 16 + 2 * 8 * n_chunks * 64 * 2 * 4
     dg = _desc(P, H_q=32, H_kv=8, sel_group=4, B=1, cu_seqlens_host=[0, 4096], budget_T_host=[2048])
     assert P.csp_reprune_workspace_bytes(dg, cap) > 1 * 32 * 64 * 256 + 2 * 4 * 1 * 8 * cap * 4   # slices of the group
 
