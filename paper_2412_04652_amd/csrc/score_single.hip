@@ -83,14 +83,12 @@ struct PipeSmem {
     static constexpr int kQ = NQB * TG::NK * 64 * 16;                      // queries in MFMA operand order
     static constexpr int off_q = kTiles;
     static constexpr int off_stat = off_q + kQ;                            // float [kSWaves][kPoll][64]: the head's statistics as loaded;
-    static constexpr int kStat = kSWaves * kPoll * 64 * 4;                 //   later the chunk's scores float [2][kPipeChunk]
-    static constexpr int off_kmod = off_stat + (kStat > 2 * kPipeChunk * 4 ? kStat : 2 * kPipeChunk * 4);  // uint32 [kSWaves][64]: modality of the keys
+    static constexpr int kStat = kSWaves * kPoll * 64 * 4;                 //   later, in each wavefront's part, fp16 [4][NQ]: the factor rows of
+    static_assert(4 * NQ * 2 <= kPoll * 64 * 4, "the factor rows fit");    //   its column-sum MFMAs
+    static constexpr int off_kmod = off_stat + kStat;                      // uint32 [kSWaves][64]: modality of the keys
     static constexpr int off_wq = off_kmod + kSWaves * 256;                // uint32 [64]: modality of the front task's window rows
     static constexpr int off_wmax = off_wq + 256;                          // float [kSWaves][NQ]: exponent references per wavefront
     static constexpr int off_wsum = off_wmax + kSWaves * NQ * 4;           // float [kSWaves][NQ]: row sums per wavefront
-    static constexpr int off_fac = off_wmax;                               // back stage (both of the above are dead by then):
-    static constexpr int kFac = kSWaves * 4 * NQ * 2;                      //   fp16 [kSWaves][4][NQ], the factor rows of the column-sum MFMAs
-    static_assert(kFac <= 2 * kSWaves * NQ * 4, "the factor rows fit where the per-wavefront maxima and sums were");
     static constexpr int off_nl = off_wsum + kSWaves * NQ * 4;             // float [NQ]: log-sum-exp of the head's rows
     static constexpr int off_zero = off_nl + NQ * 4;                       // 128 bytes of zeros: the factor rows 4..31
     static constexpr int off_flag = off_zero + 128;                        // int [kSWaves]: wavefront found its statistics
@@ -302,6 +300,8 @@ __device__ __forceinline__ float group_allreduce(float x) {
     return x;
 }
 
+template <bool V> struct Interleaved { static constexpr bool value = V; };
+
 // Modality of this lane's window row (my_row) of a task, carried from its front stage to its back stage.
 typedef uint32_t WindowBits;
 
@@ -325,6 +325,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     constexpr int kQFrags = NQB * TG::NK;                               // 1 KiB query fragments
     constexpr int kQLoads = (kQFrags + kSWaves - 1) / kSWaves;          // ... each wavefront requests
     constexpr int kTileLoads = NT * TG::NLD;
+    constexpr int kQueryLoads = kQLoads + 1;                            // loads per wavefront of request_queries
     // statistics: wavefront w merges rows w*RPW .. of the window part, lane = (row, chunk group)
     constexpr int RPW = NQ / kSWaves;                                   // rows per wavefront: 8 or 4
     constexpr int CG = kWave / RPW;                                     // chunk groups: lane takes chunks cg, cg + CG, ...
@@ -337,12 +338,11 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
 
     char* const q_lds = smem + SM::off_q;
     float* const stat_lds = reinterpret_cast<float*>(smem + SM::off_stat) + wave * (kPoll * 64);   // this wavefront's rows
-    float* const sc_lds = reinterpret_cast<float*>(smem + SM::off_stat);
     uint32_t* const kmod_lds = reinterpret_cast<uint32_t*>(smem + SM::off_kmod) + wave * 64;
     uint32_t* const wq_lds = reinterpret_cast<uint32_t*>(smem + SM::off_wq);
     float* const wmax = reinterpret_cast<float*>(smem + SM::off_wmax);
     float* const wsum = reinterpret_cast<float*>(smem + SM::off_wsum);
-    _Float16* const fac = reinterpret_cast<_Float16*>(smem + SM::off_fac) + wave * (4 * NQ);   // back stage: this wavefront's factor rows
+    _Float16* const fac = reinterpret_cast<_Float16*>(stat_lds);         // second half of the back stage: this wavefront's factor rows
     float* const nl = reinterpret_cast<float*>(smem + SM::off_nl);
     int* const flag = reinterpret_cast<int*>(smem + SM::off_flag);
     uint32_t* const fail = reinterpret_cast<uint32_t*>(smem + SM::off_fail);
@@ -366,45 +366,47 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     // ---- requests (direct to LDS; every wavefront issues the same number on every path) --------
     // the tiles this wavefront takes of the task's chunk: instruction i of a tile covers rows
     // i*RPI .. of the tile, lane l fills LDS piece (row i*RPI + l/CPR, slot l%CPR), which holds the
-    // row's piece slot ^ key(row).  A chunk that lies inside its sequence (all but the last) is
-    // addressed as uniform base + a per-lane 32-bit offset that repeats every 16 rows; rows past
-    // the end of the sequence re-read its last row.
+    // row's piece slot ^ key(row).  An instruction is addressed as a uniform base (its first row) + a
+    // per-lane 32-bit offset (the host sends token strides of 64 MiB and more to the other kernels);
+    // in a chunk that lies inside its sequence (all but the last) the offsets repeat every 16 rows and
+    // are kept; rows past the end of the sequence re-read its last row.
     constexpr int NV = 16 / TG::RPI;
     uint32_t key_voff[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i)
         key_voff[i] = (uint32_t)(lane / TG::CPR) * (uint32_t)tok_bytes + (uint32_t)(((lane % TG::CPR) ^ TG::key(i * TG::RPI + lane / TG::CPR)) * 16);
-    const bool small_stride = tok_bytes < ((int64_t)1 << 26);   // uniform
+    const int64_t row_step = (int64_t)TG::RPI * tok_bytes;   // uniform
+    struct KeyCursor { const char* at; int j; };            // uniform: the next instruction's first row, address and index
     // (loads first .. first + count - 1 of the kTileLoads, in the order tile, instruction)
-    auto request_keys = [&](const PipeRec& t, int first, int count) {
-        const char* kbase = t.kbase;
-        if (small_stride && t.c0 + kPipeChunk <= t.L) {   // uniform
+    // ... of a chunk that lies inside its sequence: no branches, so that the requests stay where they
+    // are written, between the arithmetic
+    auto request_keys_inside = [&](const PipeRec& t, KeyCursor& kc, int first, int count) {
 #pragma unroll
-            for (int t4 = 0; t4 < NT; ++t4) {
-                const char* tb0 = kbase + (int64_t)tile_j0(t, t4) * tok_bytes;
+        for (int idx = 0; idx < kTileLoads; ++idx) {
+            if (idx < first || idx >= first + count) continue;
+            const int t4 = idx / TG::NLD, i = idx % TG::NLD;
+            if (i == 0) kc.at = t.kbase + (int64_t)tile_j0(t, t4) * tok_bytes;
+            load_to_lds_16<!REUSED>(kc.at, key_voff[i % NV], tile_lds(t4) + i * 1024);
+            kc.at += row_step;
+        }
+    };
+    // ... of any chunk, all at once
+    auto request_keys_ragged = [&](const PipeRec& t) {
+        const int ln = opaque(lane);
+        const int row_in = ln / TG::CPR;
 #pragma unroll
-                for (int i = 0; i < TG::NLD; ++i) {
-                    if (t4 * TG::NLD + i < first || t4 * TG::NLD + i >= first + count) continue;
-                    load_to_lds_16<!REUSED>(tb0 + (int64_t)(i * TG::RPI) * tok_bytes, key_voff[i % NV], tile_lds(t4) + i * 1024);
-                }
-            }
-        } else {
-            const int ln = opaque(lane);
-            const int row_in = ln / TG::CPR;
-            const uint32_t row_off = (uint32_t)row_in * (uint32_t)tok_bytes;   // what key_voff holds beside the piece offset
+        for (int t4 = 0; t4 < NT; ++t4) {
+            const int j0 = tile_j0(t, t4);
 #pragma unroll
-            for (int t4 = 0; t4 < NT; ++t4) {
-                const int j0 = tile_j0(t, t4);
-#pragma unroll
-                for (int i = 0; i < TG::NLD; ++i) {
-                    if (t4 * TG::NLD + i < first || t4 * TG::NLD + i >= first + count) continue;
-                    int j = j0 + i * TG::RPI + row_in;
-                    j = j < t.L ? j : t.L - 1;
-                    load_to_lds_16<!REUSED>(kbase + (int64_t)j * tok_bytes + (key_voff[i % NV] - row_off), tile_lds(t4) + i * 1024);
-                }
+            for (int i = 0; i < TG::NLD; ++i) {
+                const int first_row = j0 + i * TG::RPI, left = t.L - 1 - first_row;   // uniform: rows of the sequence after the first
+                const uint32_t piece = (uint32_t)(((ln % TG::CPR) ^ TG::key(i * TG::RPI + row_in)) * 16);
+                const char* const at = t.kbase + (int64_t)(left > 0 ? first_row : t.L - 1) * tok_bytes;
+                load_to_lds_16<!REUSED>(at, (uint32_t)min(row_in, max(left, 0)) * (uint32_t)tok_bytes + piece, tile_lds(t4) + i * 1024);
             }
         }
     };
+    auto chunk_inside = [&](const PipeRec& t) { return t.c0 + kPipeChunk <= t.L; };   // uniform
     // the queries in MFMA operand order (fragment (mb, s) of lane l at ((mb*NK + s)*64 + l)*16; window
     // rows past the part's last re-read it: finite logits that get weight 0), and the modality of
     // the part's window rows
@@ -437,19 +439,19 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         const int j = tile_j0(t, ln >> 5) + (ln & 31);
         load_to_lds_1(t.mod, (uint32_t)(j < t.L ? j : t.L - 1), lds0 + SM::off_kmod + wave * 256);
     };
-    constexpr int kQueryLoads = kQLoads + 1;   // loads per wavefront of request_queries (request_keys: kTileLoads)
 
     // ---- front stage: logits, statistics and the published log-sum-exp of the chunk ----------
     // The chunk's keys and queries are in LDS.  When this wavefront has read its tiles for the last
     // time it requests the next ones with next_keys(first, count), a few at a time between the
     // exponentials (the memory pipeline takes a 1 KiB request every 16 cycles or so: requested in one
     // go they would stall the wavefront for thousands of cycles); after_barrier() runs when every
-    // wavefront has read the queries.
+    // wavefront has read the queries.  (front_a: up to the per-wavefront maxima and sums in LDS; after a
+    // workgroup barrier front_b publishes the chunk's log-sum-exp.)
     // On return pk holds the chunk's weights 2^15 * 2^(c*logit - wavefront maximum of the row) as fp16
     // pairs (pk[t4][mb][h]: accumulator registers 2h, 2h+1 of tile t4, query block mb), ref this
     // lane's row (my_row) of the references (maximum - 15) and win the modalities of the window rows.
-    auto front = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, const PipeRec& t, auto&& next_keys, auto&& after_barrier) {
-        const int rows = t.rows, pos0 = t.pos0, c0 = t.c0;
+    auto front_a = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, const PipeRec& t, bool next_inside, auto&& next_keys, auto&& next_keys_ragged) {
+        const int pos0 = t.pos0, c0 = t.c0;
         win = wq_lds[my_row];
         // acc[t4][mb][v] = q_i . k_j, i = mb*32 + acc_row(v, half), j = tile_j0(t4) + lane%32
         f32x16 acc[NT][NQB];
@@ -465,7 +467,6 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
 #pragma unroll
             for (int t4 = 0; t4 < NT; ++t4) kf[b2][t4] = *reinterpret_cast<const bf16x8*>(tile_ptr(t4) + (kaddr0 ^ (s_ * 32)));
         };
-        CSP_TS(2);
         fetch_keys(0, 0);
 #pragma unroll
         for (int s_ = 0; s_ < TG::NK; ++s_) {
@@ -480,7 +481,6 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
                 for (int mb = 0; mb < NQB; ++mb) acc[t4][mb] = mma(qa[mb], kf[s_ & 1][t4], s_ == 0 ? zero : acc[t4][mb]);
             __builtin_amdgcn_sched_barrier(0);
         }
-        CSP_TS(3);
         CSP_TS(4);
         // keys past the end, and keys a row may not see (causal tail)
         if (c0 + kPipeChunk > (p.causal ? pos0 : t.L)) {
@@ -521,7 +521,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         // weights in place of the logits, their row sums, and the fp16 copies that wait for the head's
         // statistics (half the registers; 11 bits are within the tolerance, and the scale keeps small
         // weights normal): a pair of accumulator registers at a time, so that few fp32 weights are live
-        {
+        auto weights = [&](auto interleave) {
             float rs[N];
 #pragma unroll
             for (int mb = 0; mb < NQB; ++mb)
@@ -529,7 +529,11 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
                 for (int v4 = 0; v4 < 4; ++v4) {
                     constexpr int kPer = kTileLoads / (NQB * 4);
                     static_assert(kPer * NQB * 4 == kTileLoads, "the requests divide evenly over the iterations");
-                    next_keys((mb * 4 + v4) * kPer, kPer);
+                    if constexpr (decltype(interleave)::value) {
+                        __builtin_amdgcn_sched_barrier(0);   // (here, not all of them ahead of the arithmetic)
+                        next_keys((mb * 4 + v4) * kPer, kPer);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                     const float4 w = *reinterpret_cast<const float4*>(wm_lane + mb * 32 + v4 * 8);
                     const float ms[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
@@ -550,11 +554,17 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
                     }
                 }
             wsum[wave * NQ + my_row] = reduce_scatter_valu<N, false>(rs, lane);
+        };
+        if (next_inside) {
+            weights(Interleaved<true>{});
+        } else {
+            next_keys_ragged();
+            weights(Interleaved<false>{});
         }
         CSP_TS(6);
-        lds_barrier();
-        after_barrier();
-        CSP_TS(7);
+    };
+    auto front_b = [&](const PipeRec& t) {
+        const int rows = t.rows;
         {
             // log-sum-exp of the chunk per row (-inf when the row sees none of its keys): wavefront w
             // takes rows w*RPW .., lane = (row, wavefront whose maximum and sum it brings in)
@@ -571,10 +581,12 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     };
 
     // ---- back stage: the head's statistics, weights, column sums, scores ----------------------
-    // The first round of statistics and the key modalities are in LDS.  before_store() runs before the
-    // scores leave for global memory.  Returns false (uniform) when the wait for the other chunks ran out.
-    auto back = [&](const f16x2 (&pk)[NT][NQB][8], float ref, const WindowBits& win, const PipeRec& t, int64_t spin, auto&& before_store) -> bool {
-        const int rows = t.rows, c0 = t.c0, n_chunks_b = rec_chunks(t);
+    // The first round of statistics and the key modalities are in LDS.  back_a merges the statistics of
+    // this wavefront's rows into the rows' log-sum-exp (LDS) and notes whether its wait ran out; after a
+    // workgroup barrier back_b turns the waiting weights into scores and stores them, or returns false
+    // (uniform) when some wavefront's wait ran out.
+    auto back_a = [&](const PipeRec& t, int64_t spin) {
+        const int rows = t.rows, n_chunks_b = rec_chunks(t);
         // (the few loads that the compiler sees, on the paths that are rarely taken: it waits for them
         // where their values are used, and with them for every load in flight)
         typedef const __attribute__((address_space(1))) float* GlobalStat;
@@ -635,22 +647,17 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             Ls = group_allreduce<CG, false>(Ls * fast_exp2(M - (Mrow == NEG_INF ? 0.f : Mrow)));
             M = Mrow;
         }
-        CSP_TS(10);
         if (lane == 0) flag[wave] = ok ? 1 : 0;
         if (st_cg == 0 && ok) {   // chunk 0 holds a visible key: M is finite
             const float Lh = fmaf(p.n_score, fast_exp2(-M), Ls);  // the n of the n-softmax, in the same scaled units
             nl[st_row] = st_row < rows ? M + fast_log2(Lh) : __builtin_inff();   // rows past the window: weight 0
         }
-        lds_barrier();
+    };
+    auto back_b = [&](const f16x2 (&pk)[NT][NQB][8], float ref, const WindowBits& win, const PipeRec& t) -> bool {
         bool all_ok = true;
 #pragma unroll
         for (int w = 0; w < kSWaves; ++w) all_ok = all_ok && flag[w] != 0;
-        if (!all_ok) {
-            before_store();
-            lds_barrier();   // the flags may be rewritten
-            return false;
-        }
-        CSP_TS(11);
+        if (!all_ok) return false;
         // Column sums on the matrix cores: (factor rows) x (weights).  The weights are the B operand as
         // they sit (keys on the lane axis; per lane and step 8 window rows).  The factor of this lane's
         // row, 2^(reference - lse), scaled into fp16's range and split into two fp16 (22 bits), goes to
@@ -686,39 +693,32 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
                     }
                 }
         }
-        CSP_TS(12);
-        // lanes 0-31 hold rows 0..3 of the product for key lane of each tile.  The score buffer is where
-        // the statistics arrived: every wavefront has read its own by now (a workgroup barrier ago)
+        // lanes 0-31 hold rows 0..3 of the product for key `lane` of each tile: they store its two scores
+        // (32 consecutive floats per tile and array)
         if (half == 0) {
+            typedef __attribute__((address_space(1))) float* GlobalScore;
             const int rank_end = t.L - p.R;  // keys >= rank_end are not ranked
 #pragma unroll
             for (int t4 = 0; t4 < NT; ++t4) {
                 const float ct = (cs[t4][0] + cs[t4][1]) * kFactorUnshift;   // over the text window rows
                 const float cv = (cs[t4][2] + cs[t4][3]) * kFactorUnshift;   // over the visual window rows
                 const bool key_text = kmod_lds[t4 * 32 + lane] == 0;
-                const bool ranked = tile_j0(t, t4) + lane < rank_end;
-                const int at = (t4 * kSWaves + wave) * kTile + lane;
-                sc_lds[at] = ranked ? (key_text ? ct : cv) : 0.f;
-                sc_lds[kPipeChunk + at] = ranked ? (key_text ? cv : ct) : 0.f;
+                const int j = tile_j0(t, t4) + lane;
+                const bool ranked = j < rank_end;
+                if (j < t.L) {
+                    const GlobalScore out_self = (GlobalScore)(t.out_self + j);
+                    out_self[0] = ranked ? (key_text ? ct : cv) : 0.f;
+                    out_self[p.cross_delta] = ranked ? (key_text ? cv : ct) : 0.f;
+                }
             }
-        }
-        lds_barrier();
-        before_store();
-        CSP_TS(13);
-        // the chunk's scores: one coalesced burst per array
-        const int nk = min(kPipeChunk, t.L - c0);
-        float* const out_self = t.out_self + c0;
-        float* const out_cross = out_self + p.cross_delta;
-        for (int i = tid; i < nk; i += kSThreads) {
-            out_self[i] = sc_lds[i];
-            out_cross[i] = sc_lds[kPipeChunk + i];
         }
         return true;
     };
 
     // ---- the pipeline -------------------------------------------------------------------------
     // Loads of a step, in issue order (per wavefront): statistics + modalities of the back task,
-    // key tiles of the next front task (kTileLoads), its queries (kQueryLoads).
+    // key tiles of the next front task (kTileLoads), its queries (kQueryLoads).  Two workgroup
+    // barriers per step: at its start and between the halves of the two stages.
     f16x2 pkA[NT][NQB][8], pkB[NT][NQB][8];
     float refA = 0.f, refB = 0.f;
     WindowBits winA = 0u, winB = 0u;
@@ -728,52 +728,62 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     {
         const PipeRec t0 = load_rec(rec_of(0));
         request_queries(t0);
-        request_keys(t0, 0, kTileLoads);
+        request_keys_ragged(t0);
         wait_loads<0>();
     }
-    // one step: front of task `it`, then back of task `it - 1`.  Records are fetched where they are
-    // needed (a scalar load each) rather than kept: scalar registers are scarce.
-    auto step = [&](f16x2 (&pk_f)[NT][NQB][8], float& ref_f, WindowBits& win_f, const f16x2 (&pk_b)[NT][NQB][8], float ref_b,
-                    const WindowBits& win_b, int it) {
+    // One step, for the tasks it, it - 1 and it - 2 of this workgroup: the scores of task it - 2 from
+    // its waiting weights and the log-sum-exps merged in the previous step; logits, weights, maxima
+    // and sums of task it; barrier; its log-sum-exp published; the published ones of task it - 1
+    // merged.  What a workgroup publishes in a step is looked for by the others in their next step,
+    // after they have published their own: they may be most of a step apart without anybody waiting.
+    // The weights of a task are consumed right before the registers are filled with those of the task
+    // two steps on.  Records are fetched where they are needed (a scalar load each) rather than
+    // kept: scalar registers are scarce.
+    auto step = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, int it) {
 #ifdef CSP_SINGLE_TIMING
         ts_it = it;
 #endif
         CSP_TS(0);
-        lds_barrier();   // the front task's queries have landed for every wavefront; the previous score burst has left the LDS
-        request_stats(load_rec(rec_of(it - 1)));
+        lds_barrier();   // the front task's queries have landed for every wavefront; the rows' log-sum-exps of task it - 2 are in LDS
         CSP_TS(1);
-        const PipeRec tn = load_rec(rec_of(it + 1));
-        auto keys_next = [&](int first, int count) { request_keys(tn, first, count); };   // this wavefront is done with its tiles
-        auto queries_next = [&]() { request_queries(tn); };  // every wavefront is done with the queries
         {
-            const PipeRec tf = load_rec(rec_of(it));
-            if (tf.valid) {
-                front(pk_f, ref_f, win_f, tf, keys_next, queries_next);
-            } else {
-                keys_next(0, kTileLoads);
-                lds_barrier();
-                queries_next();
+            const PipeRec tb = load_rec(rec_of(it - 2));
+            if (tb.valid && !back_b(pk, ref, win, tb) && tid == 0) {
+                fail[(it - 2) >> 5] |= 1u << ((it - 2) & 31);
+                atomicAdd(p.counters, 1);
             }
         }
+        CSP_TS(2);
+        request_stats(load_rec(rec_of(it - 1)));
+        const PipeRec tn = load_rec(rec_of(it + 1));
+        KeyCursor kcn;
+        auto keys_next = [&](int first, int count) { request_keys_inside(tn, kcn, first, count); };   // this wavefront is done with its tiles
+        auto keys_next_ragged = [&]() { request_keys_ragged(tn); };
+        const PipeRec tf = load_rec(rec_of(it));
+        CSP_TS(3);
+        if (tf.valid) front_a(pk, ref, win, tf, chunk_inside(tn), keys_next, keys_next_ragged);
+        else keys_next_ragged();
+        CSP_TS(7);
+        lds_barrier();   // every wavefront is done with the queries; its maxima and sums are in LDS
         CSP_TS(8);
-        wait_loads<kTileLoads + kQueryLoads>();   // the back task's statistics and modalities have landed
+        request_queries(tn);
+        if (tf.valid) front_b(tf);
         CSP_TS(9);
-        auto all_landed = [&]() { wait_loads<0>(); };   // before the stores: only loads are outstanding here
-        bool gave_up = false;
+        wait_loads<kTileLoads + kQueryLoads>();   // the statistics and modalities of task it - 1 have landed
+        CSP_TS(10);
         {
-            const PipeRec tb = load_rec(rec_of(it - 1));
-            if (tb.valid) gave_up = !back(pk_b, ref_b, win_b, tb, p.spin_ticks, all_landed);
-            else all_landed();
+            const PipeRec tm = load_rec(rec_of(it - 1));
+            if (tm.valid) back_a(tm, p.spin_ticks);
         }
-        if (gave_up && tid == 0) {
-            fail[(it - 1) >> 5] |= 1u << ((it - 1) & 31);
-            atomicAdd(p.counters, 1);
-        }
+        CSP_TS(11);
+        wait_loads<0>();   // the next task's keys and queries (this wavefront's) have landed
+        CSP_TS(12);
+        CSP_TS(13);
         CSP_TS(14);
     };
-    for (int it = 0; it <= p.n_iters; it += 2) {
-        step(pkA, refA, winA, pkB, refB, winB, it);
-        step(pkB, refB, winB, pkA, refA, winA, it + 1);
+    for (int it = 0; it <= p.n_iters + 1; it += 2) {
+        step(pkA, refA, winA, it);
+        step(pkB, refB, winB, it + 1);
     }
 
     // ---- tasks whose wait ran out: every chunk's statistics recomputed here, own chunk last ----
@@ -782,23 +792,27 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         if (!((fail[it >> 5] >> (it & 31)) & 1u)) continue;   // uniform
         const PipeRec t = load_rec(rec_of(it));
         const int ncb = rec_chunks(t), own = t.c0 / kPipeChunk;
-        auto nothing = [&]() {};
         auto no_keys = [&](int, int) {};
+        auto no_keys_ragged = [&]() {};
         for (int k = 0; k < ncb; ++k) {
             PipeRec ty = t;   // the chunks of a head part differ in their first key only
             ty.c0 = (k < ncb - 1 ? (k < own ? k : k + 1) : own) * kPipeChunk;
             lds_barrier();
             request_queries(ty);
-            request_keys(ty, 0, kTileLoads);
+            request_keys_ragged(ty);
             wait_loads<0>();
             lds_barrier();
-            front(pkA, refA, winA, ty, no_keys, nothing);
+            front_a(pkA, refA, winA, ty, false, no_keys, no_keys_ragged);
+            lds_barrier();
+            front_b(ty);
         }
         wait_loads<0>();   // this wavefront's own stores of the statistics are complete (it reads back its own rows)
         lds_barrier();
         request_stats(t);
         wait_loads<0>();
-        back(pkA, refA, winA, t, (int64_t)1 << 40, nothing);
+        back_a(t, (int64_t)1 << 40);
+        lds_barrier();
+        back_b(pkA, refA, winA, t);
     }
 }
 
@@ -844,7 +858,8 @@ hipError_t launch_score_single(ScoreParams& p, int D, hipStream_t s) {
     const int n_wg = p.n_lin < cus ? p.n_lin : cus;
     p.n_iters = (p.n_lin + n_wg - 1) / n_wg;
     // the chunks of the heads that share a KV head must be at most one step apart
-    if ((int64_t)share * p.n_chunks > n_wg || p.n_iters > kScoreSingleMaxIters) return hipErrorNotReady;
+    // (and the kernel addresses a key row as a 32-bit offset from the first row of its load instruction)
+    if ((int64_t)share * p.n_chunks > n_wg || p.n_iters > kScoreSingleMaxIters || p.k_stride_tok >= ((int64_t)1 << 25)) return hipErrorNotReady;
     // the task table follows the statistics in the workspace
     const size_t n_stats = (size_t)p.B * p.H_q * p.vsplit * p.n_chunks * kStatRows;
     p.table = reinterpret_cast<PipeRec*>(reinterpret_cast<char*>(p.part) + ((n_stats * sizeof(float) + 15) & ~(size_t)15));
