@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--no-head-averaged", action="store_true",
                     help="skip the extra pass with one index set per layer (scores summed over all heads)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the lines for the other configurations (single 4k layer, GQA ragged, 64k)")
     return ap.parse_args()
 
 
@@ -254,6 +256,9 @@ def measure(cfg, inputs, budget_frac, decode_steps, steps, warmup, device, n_str
         })
     # kept keys per (sequence, index set): below T when the two top-K sets overlap (mixed windows)
     res["kept_mean"] = float(torch.stack([l.kept_cnt[:, :, 0].float().mean() for l in layers]).mean())
+    # tasks of the last scoring launch of each layer whose wait for another workgroup's statistics ran
+    # out (they recompute them themselves, with the same result): 0 unless the chip was shared
+    res["score_fallbacks"] = int(sum(l.score_fallbacks() for l in layers))
     if decode_steps > 0:
         dec_ms = avg(ms["decode"])
         sweeps = [x / n_layers for x in ms["decode_split_sweep"]]   # per launch
@@ -314,8 +319,33 @@ def measure_reprune(cfg, inputs, budget_frac, period, cycles, device):
                 share_of_decode_time=rp / (rp + period * step), kv_len_after=kept)
 
 
+def stream_peaks(device):
+    """The library's streaming probe over 2 GiB: bytes read per second by a kernel that only reads,
+    bytes read + written per second by one that copies."""
+    import torch
+    import paper_2412_04652_amd as pkg
+    n = 1 << 31
+    src = torch.empty(n, dtype=torch.uint8, device=device).fill_(1)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(4096, dtype=torch.uint8, device=device)
+    out = {}
+    for name, d, factor in (("read", None, 1), ("copy", dst, 2)):
+        for _ in range(3):
+            pkg.csp_probe_stream(src, d, sink)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            pkg.csp_probe_stream(src, d, sink)
+        b.record()
+        torch.cuda.synchronize()
+        out[name] = 10 * factor * n / (a.elapsed_time(b) * 1e-3) / 1e9
+    del src, dst
+    torch.cuda.empty_cache()
+    return out
+
+
 def copy_peak(device):
-    """Plain device-to-device copy of 2 GiB: the achievable stream bandwidth on this machine."""
+    """Plain device-to-device copy of 2 GiB (torch's copy kernel): the achievable stream bandwidth on this machine."""
     import torch
     n = 1 << 30
     src = torch.empty(n, dtype=torch.int16, device=device).fill_(1)
@@ -331,15 +361,146 @@ def copy_peak(device):
     return 10 * 2 * n * 2 / (a.elapsed_time(b) * 1e-3) / 1e9
 
 
-def cpu_baseline(cfg, inputs, budget_frac, target_s):
-    """The CPU oracle, as it stands, on a bounded sample of (sequence, head) problems of layer 0:
-    score -> select -> gather -> one decode step each."""
+# The other configurations of the workload list (they are parity-test cases first; one line each here,
+# pruning on one stream): single 4k layer, GQA with ragged lengths, one 64k sequence with window 128.
+OTHER_CONFIGS = {
+    "7b_4k_single_layer": dict(kind="4k", B=1, H_q=32, H_kv=32, D=128, O=64, budget=0.5, sel_group=1, layers=8, steps=16, heavy=0.0),
+    "gqa_28q_4kv_ragged_8k": dict(kind="gqa", B=8, H_q=28, H_kv=4, D=128, O=64, budget=0.5, sel_group=7, layers=8, steps=16, heavy=0.0),
+    "long_64k_window_128": dict(kind="64k", B=1, H_q=32, H_kv=32, D=128, O=128, budget=0.1, sel_group=1, layers=4, steps=16, heavy=0.01),
+}
+
+
+def measure_config(name, c, device, passes=3):
+    """`layers` independent layers of the configuration (different seeds), each pruned and decoded like
+    a layer of the main workload; figures are per layer."""
     import numpy as np
+    import torch
+    import csp_workloads as W
+    from paper_2412_04652_amd.runner import CspLayer
+    rng = np.random.default_rng({"4k": 11, "gqa": 1000, "64k": 5}[c["kind"]])
+    if c["kind"] == "4k":
+        layouts = [W.layout_7b_4k() for _ in range(c["B"])]
+    elif c["kind"] == "gqa":
+        layouts = [W.layout_gqa_ragged(rng, 8192) for _ in range(c["B"])]
+    else:
+        layouts = [W.layout_64k(rng) for _ in range(c["B"])]
+    lens = [sum(n for _, n in seq) for seq in layouts]
+    budgets = [int(L * c["budget"]) for L in lens]
+    H_q, H_kv, D, O, steps = c["H_q"], c["H_kv"], c["D"], c["O"], c["steps"]
+    layers = []
+    for l in range(c["layers"]):
+        q, k, v, mod, cu_dev, cu = W.device_qkv(layouts, H_q=H_q, H_kv=H_kv, D=D, O=O, seed=l, device=device,
+                                                heavy_visual_frac=c["heavy"])
+        lay = CspLayer(dtype="bf16", H_q=H_q, H_kv=H_kv, D=D, O=O, R=O, cu_seqlens=cu.tolist(), budgets=budgets,
+                       sel_group=c["sel_group"], decode_cap=steps, device=device)
+        layers.append((q, k, v, mod, lay))
+    g = torch.Generator(device=device); g.manual_seed(779)
+    B = c["B"]
+    dq = torch.randn((B, H_q, D), generator=g, device=device).to(torch.bfloat16)
+    dk = torch.randn((B, H_kv, D), generator=g, device=device).to(torch.bfloat16)
+    dv = torch.randn((B, H_kv, D), generator=g, device=device).to(torch.bfloat16)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    spans = {"score": [], "select": [], "compact": [], "prune": [], "decode": []}
+
+    def one_pass(timed):
+        p0, p1 = ev(), ev()
+        p0.record()
+        marks = []
+        for q, k, v, mod, lay in layers:
+            e = [ev() for _ in range(4)]
+            e[0].record(); lay.score(q, k, mod)
+            e[1].record(); lay.select(mod)
+            e[2].record(); lay.compact(k, v)
+            e[3].record()
+            marks.append(e)
+        p1.record()
+        d0, d1 = ev(), ev()
+        d0.record()
+        for _ in range(steps):
+            for *_, lay in layers:
+                lay.decode_step(dq, dk, dv)
+        d1.record()
+        torch.cuda.synchronize()
+        if timed:
+            spans["prune"].append(p0.elapsed_time(p1) / len(layers))
+            spans["decode"].append(d0.elapsed_time(d1) / (len(layers) * steps))
+            for e in marks:
+                for i, kname in enumerate(("score", "select", "compact")):
+                    spans[kname].append(e[i].elapsed_time(e[i + 1]))
+
+    for _ in range(2):
+        one_pass(False)
+    for _ in range(passes):
+        one_pass(True)
+    e2, Hs = 2, H_q // c["sel_group"]
+    by = dict(score=sum(H_kv * L * D * e2 + H_q * O * D * e2 + L + 2 * Hs * (L - O) * 4 for L in lens),
+              select=sum(2 * Hs * (L - O) * 4 + Hs * T * 4 for L, T in zip(lens, budgets)),
+              compact=sum(4 * H_kv * T * D * e2 + Hs * T * 4 for T in budgets))
+    by_decode = sum(2 * H_kv * (T + (steps + 1) / 2.0) * D * e2 + H_q * D * (e2 + 4) for T in budgets)
+    avg = lambda xs: sum(xs) / len(xs)
+    prune_ms = avg(spans["prune"])
+    res = dict(config=f"{name}: B{B} x {H_q} query / {H_kv} KV heads x D{D}, lengths {min(lens)}..{max(lens)}, window {O}, "
+                      f"budget {c['budget']:g}, one index set per {c['sel_group']} query heads, {len(layers)} independent layers",
+               tokens=sum(lens), prune_ms_per_layer=prune_ms, tokens_per_s=sum(lens) / (prune_ms * 1e-3),
+               prune_gbps=sum(by.values()) / (prune_ms * 1e-3) / 1e9,
+               prune_frac_of_peak=sum(by.values()) / (prune_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+               decode_ms_per_layer_step=avg(spans["decode"]), decode_gbps=by_decode / (avg(spans["decode"]) * 1e-3) / 1e9,
+               score_fallbacks=int(sum(lay.score_fallbacks() for *_, lay in layers)),
+               kernels={k: dict(ms=avg(spans[k]), gbps=by[k] / (avg(spans[k]) * 1e-3) / 1e9, bytes=by[k]) for k in by})
+    del layers
+    torch.cuda.empty_cache()
+    return res
+
+
+REL_TOL, ABS_FLOOR = 2e-3, 1e-6    # the parity bar of the tests: relative error of a score, floor as a fraction of the largest
+
+
+def _same_result(a_s, a_c, idx, m, g_self, g_cross, g_idx, L, R):
+    """The GPU's scores and kept indices of one (sequence, head) problem against the oracle's, to the bar
+    of the parity tests: scores within REL_TOL; the same kept set except for keys whose oracle score is
+    within REL_TOL of the threshold of their region (windows of one modality)."""
+    import numpy as np
+    P = L - R
+    for g, r in ((g_self, a_s), (g_cross, a_c)):
+        tol = REL_TOL * np.abs(r[:P]) + ABS_FLOOR * np.abs(r[:P]).max()
+        if (np.abs(g[:P] - r[:P]) > tol).any():
+            return False
+    if len(g_idx) != len(idx) or (np.diff(g_idx) <= 0).any():
+        return False
+    diff = sorted(set(g_idx.tolist()) ^ set(idx.tolist()))
+    qmod = int(m[L - 1])
+    for mm in (0, 1):
+        score = a_s if mm == qmod else a_c
+        kept = [j for j in idx.tolist() if j < P and m[j] == mm]
+        mine = [j for j in diff if m[j] == mm]
+        if not mine:
+            continue
+        if not kept:
+            return False
+        tau = min(score[j] for j in kept)
+        if any(abs(score[j] - tau) > REL_TOL * tau + ABS_FLOOR * float(score[:P].max()) for j in mine):
+            return False
+    return True
+
+
+def cpu_baseline(cfg, inputs, budget_frac, target_s, device):
+    """The CPU oracle, as it stands, on a bounded sample of (sequence, head) problems of layer 0:
+    score -> select -> gather -> one decode step each.  The GPU's result for the same problems (layer 0
+    pruned once more, outside any timed region) is compared with the oracle's on the way."""
+    import numpy as np
+    import torch
     from oracle import csp_oracle as orc
     L, O, D, H = cfg["L"], cfg["O"], cfg["D"], cfg["H"]
     T = int(L * budget_frac)
     inp = inputs[0]
     threads = orc.max_threads()
+    lay0 = make_layers(cfg, inputs[:1], budget_frac, 0, device)[0][0]
+    lay0.prune(inp["q"], inp["k"], inp["v"], inp["mod"])
+    torch.cuda.synchronize()
+    gpu_self, gpu_cross = lay0.score_self.cpu().numpy(), lay0.score_cross.cpu().numpy()
+    gpu_idx, gpu_cnt = lay0.kept_idx.cpu().numpy(), lay0.kept_cnt.cpu().numpy()
+    del lay0
+    checked = {"n": 0, "bad": 0}
 
     def fetch_range(start, n):
         qs, ks, vs, ms = [], [], [], []
@@ -353,22 +514,34 @@ def cpu_baseline(cfg, inputs, budget_frac, target_s):
             ms.append(inp["mod"][lo:lo + L].cpu().numpy())
         return np.stack(qs), np.stack(ks), np.stack(vs), np.stack(ms)
 
-    def run(q, k, v, m):
+    def run(q, k, v, m, start=None):
         t0 = time.perf_counter()
         a_s, a_c = orc.scores_batch(q, k, m, O, 0.0, True)
         dq = np.ones((q.shape[0], D))
-        kc, vc = [], []
+        kc, vc, kept = [], [], []
         for p in range(q.shape[0]):
             idx, _ = orc.select(a_s[p], a_c[p], m[p], O, O, T, 0.5)
+            kept.append(idx)
             kc.append(orc.gather(k[p], idx)); vc.append(orc.gather(v[p], idx))
         orc.decode_batch(dq, np.stack(kc), np.stack(vc), 1.0)
-        return time.perf_counter() - t0
+        dt = time.perf_counter() - t0
+        if start is not None:   # (not part of the oracle's time)
+            for p in range(q.shape[0]):
+                b, h = divmod(start + p, H)
+                b %= cfg["B"]
+                lo = inp["cu"][b]
+                n = int(gpu_cnt[b, h, 0])
+                ok = _same_result(a_s[p], a_c[p], kept[p], m[p], gpu_self[h, lo:lo + L], gpu_cross[h, lo:lo + L],
+                                  gpu_idx[b, h, :n], L, O)
+                checked["n"] += 1
+                checked["bad"] += 0 if ok else 1
+        return dt
 
     # batches of 4 problems per thread (different heads each time) until the time target is met
     per_batch, n, t1, start = 4 * threads, 0, 0.0, 0
     while t1 < target_s and n < 256 * threads:
         q, k, v, m = fetch_range(start, per_batch)
-        t1 += run(q, k, v, m)
+        t1 += run(q, k, v, m, start)
         n += per_batch
         start += per_batch
     seq_layers = n / H                             # one (layer, sequence) needs all H heads
@@ -388,6 +561,7 @@ def cpu_baseline(cfg, inputs, budget_frac, target_s):
         pass
     return dict(value=seq_layers * L / t1, unit="tokens/s", cores=threads, kind="oracle", cpu_model=model,
                 one_thread_value=(2 / H) * L / t_one,
+                parity_checked=checked["n"], mismatches=checked["bad"],
                 sample=f"{n} (sequence, head) problems of layer 0 at L={L}: score+select+gather and one decode step each, "
                        f"{t1:.1f} s of wall time on {threads} OpenMP threads, scaled linearly (heads are independent)")
 
@@ -440,8 +614,14 @@ def main():
     reprune = None
     if not args.no_variants and args.workload == "7b_16k" and args.sel_group == 1:
         reprune = measure_reprune(cfg, inputs[:8], args.budget, cfg["O"], 2, device)
+    others = None
+    if not args.no_other_configs and args.workload == "7b_16k":
+        del inputs[8:]                              # (the passes below need the first layers only)
+        torch.cuda.empty_cache()
+        others = {name: measure_config(name, c, device) for name, c in OTHER_CONFIGS.items()}
     peak_copy = copy_peak(device)
-    cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds)
+    peaks = stream_peaks(device)
+    cpu = None if args.no_cpu_baseline else cpu_baseline(cfg, inputs, args.budget, args.cpu_seconds, device)
 
     # dominant kernel of the step by time
     kern = main_res["kernels"]
@@ -476,6 +656,9 @@ def main():
         "step_hbm_gbps": main_res.get("step_gbps"),
         "step_frac_of_peak": (main_res.get("step_gbps") or 0.0) / HBM_PEAK_GBPS,
         "copy_peak_gbps": peak_copy,
+        "read_peak_gbps": peaks["read"], "copy_probe_gbps": peaks["copy"],
+        "score_frac_of_read_peak": kern["score"]["gbps"] / peaks["read"],
+        "score_fallbacks": main_res["score_fallbacks"],
         "prune_frac_of_copy_peak": main_res["prune_gbps"] / peak_copy,
         "decode_frac_of_copy_peak": (main_res.get("decode_gbps") or 0.0) / peak_copy,
         "head_tokens_per_s": main_res["tokens_per_s"] * cfg["H"],
@@ -485,12 +668,14 @@ def main():
     }
     if second is not None:
         out["second_budget"] = {k: second[k] for k in ("budget", "T", "prune_ms", "tokens_per_s", "prune_gbps",
-                                                       "decode_gbps", "decode_ms_per_token") if k in second}
+                                                       "decode_gbps", "decode_ms_per_token", "score_fallbacks") if k in second}
         out["second_budget"]["kernels"] = second["kernels"]
     if variants is not None:
         out["variants_8_layers"] = variants
     if reprune is not None:
         out["reprune_while_decoding_8_layers"] = reprune
+    if others is not None:
+        out["other_configs"] = others
     if head_avg is not None:
         out["head_averaged"] = {k: head_avg[k] for k in ("budget", "T", "sel_group", "prune_ms", "tokens_per_s", "prune_gbps")}
         out["head_averaged"]["kernels"] = head_avg["kernels"]

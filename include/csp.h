@@ -95,6 +95,15 @@ const char* csp_strerror(int code);
 /* Library version string (static). */
 const char* csp_version(void);
 
+/* Measurement aid, no part of the method: streams `bytes` (a multiple of 16) from src at the
+ * rate the memory system allows.  With dst != NULL the data is copied there; with dst == NULL it
+ * is only read (folded into a few words that are XORed into sink).  The benchmark reports the
+ * two rates beside the kernels' figures as the ceilings of the box it ran on.
+ *   src, dst  device, 16-byte aligned, `bytes` long
+ *   sink      device, 4 KiB, caller-initialised
+ * Returns CSP_EINVAL for a null or misaligned pointer or a size that is not a multiple of 16. */
+int csp_probe_stream(const void* src, void* dst, size_t bytes, void* sink, void* stream);
+
 /* ------------------------------------------------------------------------
  * csp_score — Eq. "A = softmax(QK^T/sqrt d)" (or Eq. "n-softmax" when
  * n_score > 0) for the last O queries against every cached key, then the

@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = [
     "csp_decode_workspace_bytes", "csp_decode_attn", "csp_static_scratch_bytes", "csp_decode_attn_static", "csp_decode_step", "csp_decode_step_phase",
     "csp_append_kv",
     "csp_gather_modality", "csp_window_push", "csp_decode_step_window", "csp_reprune_workspace_bytes", "csp_reprune",
+    "csp_probe_stream",
 ]
 
 
@@ -81,6 +82,7 @@ def load_library():
         L.csp_append_kv.argtypes = [dp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp]; L.csp_append_kv.restype = C.c_int
         L.csp_gather_modality.argtypes = [dp, vp, vp, i32, vp, vp, i32, vp]; L.csp_gather_modality.restype = C.c_int
         L.csp_window_push.argtypes = [dp, vp, vp, i32, vp]; L.csp_window_push.restype = C.c_int
+        L.csp_probe_stream.argtypes = [vp, vp, C.c_size_t, vp, vp]; L.csp_probe_stream.restype = C.c_int
         L.csp_decode_step_window.argtypes = [dp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, vp, vp, i32, vp, sz, vp]
         L.csp_decode_step_window.restype = C.c_int
         L.csp_reprune_workspace_bytes.argtypes = [dp, i32]; L.csp_reprune_workspace_bytes.restype = sz
@@ -241,6 +243,12 @@ def csp_gather_modality(desc: Desc, modality, kept_idx, kept_cap: int, kept_cnt,
 def csp_window_push(desc: Desc, q_new, q_ring, slot: int, stream=None) -> None:
     _check(load_library().csp_window_push(desc.ref(), _ptr(q_new), _ptr(q_ring), int(slot), _stream(stream)),
            "csp_window_push")
+
+
+def csp_probe_stream(src, dst, sink, stream=None) -> None:
+    """Reads all of `src` (dst None) or copies it to `dst`: the box's read / copy rate (measurement aid)."""
+    _check(load_library().csp_probe_stream(_ptr(src), _ptr(dst) if dst is not None else None, _nbytes(src), _ptr(sink),
+                                           _stream(stream)), "csp_probe_stream")
 
 
 def csp_reprune_workspace_bytes(desc: Desc, cache_cap: int) -> int:

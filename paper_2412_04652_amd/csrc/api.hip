@@ -457,4 +457,9 @@ int csp_reprune(const csp_desc* d, const void* q_ring, int32_t ring_start, void*
     return launch_reprune_move(rp, c.row_bytes, st) == hipSuccess ? CSP_OK : CSP_EHIP;
 }
 
+int csp_probe_stream(const void* src, void* dst, size_t bytes, void* sink, void* stream) {
+    if (!src || !sink || bytes == 0 || bytes % 16 != 0 || !aligned16(src) || (dst && !aligned16(dst))) return CSP_EINVAL;
+    return launch_probe_stream(src, dst, bytes, static_cast<uint32_t*>(sink), static_cast<hipStream_t>(stream)) == hipSuccess ? CSP_OK : CSP_EHIP;
+}
+
 }  // extern "C"

@@ -93,6 +93,44 @@ hipError_t launch_compact(const CompactParams& p, int row_bytes, hipStream_t s) 
     }
 }
 
+// ---- measurement aid: the rate at which this device streams a buffer --------------------------
+// Every lane reads 16 bytes at a time (non-temporal), 4 reads in flight, workgroups stride over
+// the buffer; the data is copied to dst, or, with dst == nullptr, folded into one word per
+// workgroup (so that the reads are not optimised away) that is written to sink.
+namespace {
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void probe_stream_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n16, uint32_t* sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    uint32_t acc = 0;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        u32x4_t a[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) a[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (dst) __builtin_nontemporal_store(a[u], dst + i + u * stride);
+            else acc ^= a[u].x ^ a[u].y ^ a[u].z ^ a[u].w;
+        }
+    }
+    for (; i < n16; i += stride) {
+        const u32x4_t a = __builtin_nontemporal_load(src + i);
+        if (dst) __builtin_nontemporal_store(a, dst + i);
+        else acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    if (!dst) {
+        for (int d = 32; d > 0; d >>= 1) acc ^= __shfl_xor(acc, d);
+        if ((threadIdx.x & 63) == 0) atomicXor(sink + blockIdx.x % 1024, acc);
+    }
+}
+}  // namespace
+
+hipError_t launch_probe_stream(const void* src, void* dst, size_t bytes, uint32_t* sink, hipStream_t s) {
+    hipLaunchKernelGGL(probe_stream_kernel, dim3(256 * 16), dim3(256), 0, s, reinterpret_cast<const u32x4_t*>(src),
+                       reinterpret_cast<u32x4_t*>(dst), bytes / 16, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_append(const AppendParams& p, hipStream_t s) {
     hipLaunchKernelGGL(append_kernel, dim3(p.H_kv, p.B), dim3(64), 0, s, p);
     return hipGetLastError();

@@ -203,6 +203,7 @@ struct WindowParams {
 hipError_t launch_score(const ScoreParams& p, int dtype, int D, int max_seqlen, hipStream_t s);
 hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s);
 hipError_t launch_compact(const CompactParams& p, int row_bytes, hipStream_t s);
+hipError_t launch_probe_stream(const void* src, void* dst, size_t bytes, uint32_t* sink, hipStream_t s);
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_decode(const DecodeParams& p, int dtype, int D, hipStream_t s);
 hipError_t launch_mod_gather(const ModGatherParams& p, hipStream_t s);

@@ -465,11 +465,18 @@ __global__ __launch_bounds__(kThreads, NQB <= 2 ? CSP_SCORE_WPE_B : 1) void scor
 }
 
 // Sum of the per-slice arrays of a split selection group, slices in ascending order
-// (a fixed order: the result does not depend on scheduling).
+// (a fixed order: the result does not depend on scheduling).  Cache form: only what the scoring
+// kernels wrote is read and written (positions below the live length of sequences that are pruned).
 __global__ __launch_bounds__(256) void score_slice_sum_kernel(ScoreParams p) {
     const size_t n = (size_t)p.score_elems;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
+    if (p.view.kv_len != nullptr) {
+        const int j = (int)(i % (size_t)p.view.cap);
+        const int bs = (int)(i / (size_t)p.view.cap), b = bs / p.view.H_sel, sg = bs % p.view.H_sel;
+        const int L = view_len(p.view, b, (sg * p.sel_group) / p.G);
+        if (j >= L || view_fits(p.view, b, L)) return;
+    }
     const float* src = blockIdx.y == 0 ? p.slice_self : p.slice_cross;
     float acc = __builtin_nontemporal_load(src + i);
     for (int sl = 1; sl < p.gsplit; ++sl) acc += __builtin_nontemporal_load(src + (size_t)sl * n + i);

@@ -25,6 +25,64 @@ def from_dev_bits(t: torch.Tensor, dtype: str) -> np.ndarray:
     return t.contiguous().cpu().numpy()
 
 
+# ---- guard bands -------------------------------------------------------------------------------
+# Every buffer a layer hands to the library (outputs, workspaces, caches) is re-seated inside a larger
+# allocation with GUARD bytes of a known pattern on both sides; after each GPU test the pattern must be
+# intact (tests/conftest.py): a kernel that writes outside what it was given fails the test that ran it.
+GUARD = 4096
+CANARY = 0xA5
+_GUARDED_FIELDS = ("score_self", "score_cross", "ws_score", "kept_idx", "kept_cnt", "k_cache", "v_cache", "kv_len",
+                   "ws_decode", "out", "mod_cache", "q_ring", "rp_self", "rp_cross", "rp_idx", "rp_cnt", "ws_reprune")
+_LIVE = []   # (name, whole allocation, payload bytes) of the layers guarded since the last check
+
+
+def guard_layer(layer) -> None:
+    for name in _GUARDED_FIELDS:
+        t = getattr(layer, name, None)
+        if t is None:
+            continue
+        n = t.numel() * t.element_size()
+        whole = torch.full((n + 2 * GUARD,), CANARY, dtype=torch.uint8, device=t.device)
+        inner = whole[GUARD:GUARD + n].view(t.dtype).view(t.shape)
+        inner.copy_(t)   # (kv_len and the re-pruning state start from defined values)
+        setattr(layer, name, inner)
+        _LIVE.append((name, whole, n))
+
+
+_ORIG_INIT = None
+
+
+def install_guards() -> None:
+    """From now on every CspLayer that is built has its buffers guarded (until remove_guards)."""
+    global _ORIG_INIT
+    if _ORIG_INIT is None:
+        _ORIG_INIT = CspLayer.__init__
+
+        def guarded_init(self, *a, **kw):
+            _ORIG_INIT(self, *a, **kw)
+            guard_layer(self)
+
+        CspLayer.__init__ = guarded_init
+
+
+def remove_guards() -> None:
+    global _ORIG_INIT
+    if _ORIG_INIT is not None:
+        CspLayer.__init__ = _ORIG_INIT
+        _ORIG_INIT = None
+
+
+def check_guards() -> None:
+    """Asserts that no guard band of the layers guarded since the last call was written to."""
+    try:
+        for name, whole, n in _LIVE:
+            lo, hi = whole[:GUARD], whole[GUARD + n:]
+            assert bool((lo == CANARY).all()), f"{name}: bytes in front of the buffer were overwritten"
+            assert bool((hi == CANARY).all()), f"{name}: bytes behind the buffer were overwritten"
+    finally:
+        _LIVE.clear()
+
+
 class DeviceCase:
     def __init__(self, case, decode_cap: int = 0, device="cuda:0", reprune: bool = False, score_wait_us: int = 0):
         self.case = case

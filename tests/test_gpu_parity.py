@@ -538,13 +538,14 @@ def test_end_to_end_mixed_window_counts(gpu, oracle):
     for h in range(2):
         res = oracle.prune_group(case, 0, h)
         assert cnt[0, h, 1:3].tolist() == [res["counts"]["K_s"], res["counts"]["K_c"]] == [184, 184]
-        # overlap is data dependent and scores differ in the last bits: allow +-3 around the oracle's count
-        assert abs(int(cnt[0, h, 0]) - res["counts"]["kept"]) <= 3
         assert int(cnt[0, h, 0]) == 400 - int(cnt[0, h, 3])
         n = int(cnt[0, h, 0])
         idx = dc.layer.kept_idx[0, h].cpu().numpy()
-        assert (np.diff(idx[:n]) > 0).all() and (idx[n:] == -1).all()
-        assert len(set(idx[:n].tolist()) ^ set(res["idx"].tolist())) <= 6
+        assert (idx[n:] == -1).all()
+        # the kept set is the union of the two top-K sets: a key kept by one side only must score within the
+        # tolerance of one of the two thresholds (so the count may differ from the oracle's by such keys only)
+        a_s, a_c = oracle.group_scores(case, 0, h)
+        U.assert_kept_equivalent_mixed(idx[:n], res["idx"], a_s, a_c, 184, 184, 940, 32, f"mixed window h{h}")
         assert int(dc.layer.kv_len[0, h]) == n
 
 
@@ -681,3 +682,26 @@ def test_determinism(gpu):
     torch.cuda.synchronize()
     assert torch.equal(a[0], dc.layer.score_self) and torch.equal(a[1], dc.layer.kept_idx)
     assert torch.equal(a[2].view(torch.int16), dc.layer.k_cache.view(torch.int16))
+
+
+def test_guard_bands_notice_a_stray_write(gpu, oracle):
+    """The guard bands that every GPU test puts around a layer's buffers (tests/conftest.py): a byte
+    written just outside a buffer (here by the test itself, inside its own allocation) is reported."""
+    U = _util()
+    case = _score_case("guards")
+    dc = U.DeviceCase(case)
+    dc.layer.prune(dc.q_win, dc.k, dc.v, dc.modality)
+    torch.cuda.synchronize()
+    live = list(U._LIVE)
+    assert {name for name, _, _ in live} >= {"score_self", "score_cross", "kept_idx", "kept_cnt", "k_cache", "v_cache", "ws_score"}
+    U.check_guards()                      # intact after a pruning pass (and the list is cleared)
+    name, whole, n = next(x for x in live if x[0] == "kept_idx")
+    U._LIVE.append((name, whole, n))
+    whole[U.GUARD + n] = 0                # first byte behind the buffer
+    with pytest.raises(AssertionError, match="behind the buffer"):
+        U.check_guards()
+    U._LIVE.append((name, whole, n))
+    whole[U.GUARD + n] = U.CANARY
+    whole[U.GUARD - 1] = 0                # last byte in front of it
+    with pytest.raises(AssertionError, match="in front of the buffer"):
+        U.check_guards()

@@ -171,8 +171,20 @@ def test_reprune_cycles(gpu, oracle, name):
             t += 1
         torch.cuda.synchronize()
         before = _snapshot(U, lay, case.dtype)
+        # the score arrays hold a sentinel: only the positions of live keys of sequences that are pruned may change
+        # (also when a selection group is summed from per-slice arrays)
+        lay.rp_self.fill_(-7.0); lay.rp_cross.fill_(-7.0)
+        live = lay.kv_len.cpu().numpy()
         lay.reprune()
         torch.cuda.synchronize()
+        kv_per_sel = max(case.sel_group // (case.H_q // case.H_kv), 1)
+        for arr in (lay.rp_self.cpu().numpy(), lay.rp_cross.cpu().numpy()):
+            for b in range(case.B):
+                for s_ in range(lay.H_sel):
+                    n_live = int(live[b, s_ * kv_per_sel])
+                    written = n_live if n_live > budgets[b] else 0
+                    assert (arr[b, s_, written:] == -7.0).all(), f"{name} cycle {ci}: scores past the live keys of b{b} s{s_} were written"
+                    assert (arr[b, s_, :written] != -7.0).all()
         _check_reprune(U, oracle, lay, before, _window(case, t), dtype=case.dtype, H_q=case.H_q, H_kv=case.H_kv,
                        sel_group=case.sel_group, O=case.O, R=case.R, budgets=budgets, n_score=case.n_score,
                        cross_ratio=case.cross_ratio, sample=sample, what=f"{name} cycle {ci}")
