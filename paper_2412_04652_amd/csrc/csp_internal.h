@@ -69,15 +69,15 @@ __device__ __forceinline__ int64_t view_key0(const SeqView& v, int b, int64_t k_
 // ---- launch parameter blocks ------------------------------------------------
 // a record of the single-read score kernel's task table (see score_single.hip)
 struct alignas(16) PipeRec {
-    int32_t valid;         // 0: nothing to compute (the addresses below still point at readable memory)
+    int32_t rows_valid;    // window rows of the part (low 16 bits); bit 16 clear: nothing to compute (the addresses
+                           // below still point at readable memory)
     int32_t L;             // keys of the sequence, at least 1
     int32_t c0;            // first key of the chunk
-    int32_t rows;          // window rows of the part
     int32_t pos0;          // absolute position of the part's window row 0
-    int32_t spare;
+    uint32_t spare0, spare1;
     const char* kbase;     // key row 0 of the sequence, this KV head
     const char* qpart;     // query row 0 of the part
-    const uint8_t* mod;    // modality of key 0 of the sequence
+    const uint32_t* kbits; // modality of the chunk's keys, a word per 32 keys (bit j % 32 of word j / 32: key c0 + j is visual)
     float* stat;           // statistics of the head part: chunk 0, row 0
     float* out_self;       // self score of key 0 in the array this task writes (cross: + ScoreParams::cross_delta)
 };
@@ -97,6 +97,8 @@ struct ScoreParams {
     int32_t single_chunks, vsplit;  // single read: 512-key chunks per sequence; parts of <= 64 window rows
     int32_t n_tasks, n_lin, n_iters;  // single read: tasks, padded task ids, pipeline steps (filled in by the launcher)
     PipeRec* table;            // single read: task table in the workspace, n_lin + 1 records (filled in by the launcher)
+    uint32_t* modbits;         // single read: behind the table, the keys' modality as bits (see score_single.hip; written by
+                               // the set-up kernel of the launch)
     int64_t cross_delta;              // single read: elements from the self score array (or slices) to the cross one
     int32_t D;                        // single read: head dimension
     float* slice_base;    // first of the per-slice score arrays in the workspace (slice_self/slice_cross are derived)

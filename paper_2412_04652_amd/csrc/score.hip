@@ -576,8 +576,10 @@ ScorePlan score_plan(int B, int H_q, int H_kv, int sel_group, int max_seqlen, in
                      tasks <= (int64_t)256 * kScoreSingleMaxIters;
     // ... and a 64-byte record per task (ids padded to a multiple of 8 * G * parts, plus one)
     const int64_t share8 = (int64_t)8 * G * pl.vsplit;
+    // ... and the keys' modality as bits, a word per 32 keys, per (sequence, selection group)
     const size_t one_pass = up((size_t)B * H_q * pl.vsplit * pl.single_chunks * 64 * sizeof(float)) +
-                            (size_t)((tasks + share8 - 1) / share8 * share8 + 1) * kScoreSingleRecBytes;
+                            (size_t)((tasks + share8 - 1) / share8 * share8 + 1) * kScoreSingleRecBytes +
+                            ((size_t)B * (H_q / sel_group) * pl.single_chunks * 16 + 2) * sizeof(uint32_t);
     pl.single = can && !have_row_lse;
     // csp_score_lse shares the size; 16 bytes of counters in front
     pl.part_bytes = 16 + (can && one_pass > two_pass ? one_pass : two_pass);

@@ -85,9 +85,7 @@ struct PipeSmem {
     static constexpr int off_stat = off_q + kQ;                            // float [kSWaves][kPoll][64]: the head's statistics as loaded;
     static constexpr int kStat = kSWaves * kPoll * 64 * 4;                 //   later, in each wavefront's part, fp16 [4][NQ]: the factor rows of
     static_assert(4 * NQ * 2 <= kPoll * 64 * 4, "the factor rows fit");    //   its column-sum MFMAs
-    static constexpr int off_kmod = off_stat + kStat;                      // uint32 [kSWaves][64]: modality of the keys
-    static constexpr int off_wq = off_kmod + kSWaves * 256;                // uint32 [64]: modality of the front task's window rows
-    static constexpr int off_wmax = off_wq + 256;                          // float [kSWaves][NQ]: exponent references per wavefront
+    static constexpr int off_wmax = off_stat + kStat;                      // float [kSWaves][NQ]: exponent references per wavefront
     static constexpr int off_wsum = off_wmax + kSWaves * NQ * 4;           // float [kSWaves][NQ]: row sums per wavefront
     static constexpr int off_nl = off_wsum + kSWaves * NQ * 4;             // float [NQ]: log-sum-exp of the head's rows
     static constexpr int off_zero = off_nl + NQ * 4;                       // 128 bytes of zeros: the factor rows 4..31
@@ -105,6 +103,13 @@ struct PipeSmem {
 // issues no vector load of its own, and it has few scalar registers to spare for descriptors.)
 static_assert(sizeof(PipeRec) == 64, "one record = one 16-dword scalar load");
 
+// The keys' modality as bits: a row of bits_words words per sequence (packed form: every selection
+// group of a sequence sees the same flags) or per (sequence, selection group) (cache form), bit
+// j % 32 of word j / 32 = key j is a visual token; keys past the end: 0; two spare words at the end.
+__device__ __host__ __forceinline__ int bits_words(const ScoreParams& p) { return p.n_chunks * (kScoreSingleChunk / 32); }
+__device__ __forceinline__ int bits_row(const SeqView& v, int b, int sg) { return v.kv_len ? b * v.H_sel + sg : b; }
+__device__ __host__ __forceinline__ size_t bits_rows(const ScoreParams& p) { return (size_t)p.B * (p.view.kv_len ? p.view.H_sel : 1); }
+
 // record of task id `lin` (ids at or past n_lin: a record that is not valid)
 __device__ PipeRec make_rec(const ScoreParams& p, int lin) {
     PipeRec t;
@@ -121,16 +126,17 @@ __device__ PipeRec make_rec(const ScoreParams& p, int lin) {
     const int L = view_len(p.view, b, hk);
     t.L = L > 0 ? L : 1;
     t.c0 = chunk * kPipeChunk;
-    t.valid = real && L > 0 && t.c0 < L && !view_fits(p.view, b, L);
-    if (!t.valid) t.c0 = 0;
+    const bool valid = real && L > 0 && t.c0 < L && !view_fits(p.view, b, L);
+    if (!valid) t.c0 = 0;
     const int row0 = v * kStatRows;
-    t.rows = min(kStatRows, p.O - row0);
+    const int rows = min(kStatRows, p.O - row0);
+    t.rows_valid = rows | (valid ? 1 << 16 : 0);
     t.pos0 = t.L - p.O + row0;
-    t.spare = 0;
     const int bh = b * p.H_q + hq;
     t.kbase = reinterpret_cast<const char*>(p.k) + (view_key0(p.view, b, p.k_stride_tok) + (int64_t)hk * p.k_stride_head) * 2;
     t.qpart = reinterpret_cast<const char*>(p.q_win) + ((size_t)bh * p.O + row0) * p.D * 2;
-    t.mod = p.modality + view_mod0(p.view, b, sg);
+    t.kbits = p.modbits + (size_t)bits_row(p.view, b, sg) * bits_words(p) + (t.c0 / kPipeChunk) * (kPipeChunk / 32);
+    t.spare0 = t.spare1 = 0u;
     t.stat = p.part + ((size_t)(bh * p.vsplit + v) * p.n_chunks) * kStatRows;
     const int slice = (hq % p.sel_group) * p.vsplit + v;
     t.out_self = (p.gsplit > 1 ? p.slice_self + (size_t)slice * (size_t)p.score_elems : p.score_self) + (size_t)view_score0(p.view, b, sg);
@@ -138,31 +144,67 @@ __device__ PipeRec make_rec(const ScoreParams& p, int lin) {
 }
 
 // Set-up of a launch: every statistic marked as not yet published, the counters cleared, the
-// task table written (n_lin records and one that is not valid).
+// task table written (n_lin records and one that is not valid), the keys' modality flags packed
+// into bits (a word per 32 keys of a (sequence, selection group); keys past the end: 0).
 __global__ __launch_bounds__(256) void score_single_setup_kernel(ScoreParams p) {
     const size_t n = (size_t)p.B * p.H_q * p.vsplit * p.n_chunks * kStatRows;
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i < n) reinterpret_cast<uint32_t*>(p.part)[i] = 0x7fc00000u;   // a NaN, by its bit pattern
     if (i < 4) p.counters[i] = 0;
     if (i <= (size_t)p.n_lin) p.table[i] = make_rec(p, (int)i);
+    const size_t keys_per_row = (size_t)bits_words(p) * 32;
+    if (i < bits_rows(p) * keys_per_row) {   // (a multiple of 64: whole wavefronts)
+        const int j = (int)(i % keys_per_row), row = (int)(i / keys_per_row);
+        const int b = p.view.kv_len ? row / p.view.H_sel : row, sg = p.view.kv_len ? row % p.view.H_sel : 0;
+        const int L = view_len(p.view, b, (sg * p.sel_group) / p.G);
+        const bool vis = j < L && p.modality[view_mod0(p.view, b, sg) + j] != 0;
+        const uint64_t bal = __ballot(vis);
+        if ((threadIdx.x & 31) == 0) p.modbits[i / 32] = (uint32_t)(bal >> (threadIdx.x & 32));
+    }
+    if (i < 2) p.modbits[bits_rows(p) * bits_words(p) + i] = 0u;
 }
 
-// The record at `rec`, through the scalar cache (written by the previous kernel, never by this one).
+// A task as the kernel uses it: the record at `rec`, through the scalar cache (written by the previous
+// kernel, never by this one), its packed fields taken apart.
+struct PipeTask {
+    int32_t valid, L, c0, rows, pos0;
+    const char* kbase;
+    const char* qpart;
+    const uint32_t* kbits;
+    float* stat;
+    float* out_self;
+};
 typedef int i32x16 __attribute__((ext_vector_type(16)));
-__device__ __forceinline__ PipeRec load_rec(const PipeRec* rec) {
+__device__ __forceinline__ PipeTask load_rec(const PipeRec* rec) {
     i32x16 v;
     asm volatile("s_load_dwordx16 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(rec) : "memory");
     auto ptr = [&](int i) { return ((uint64_t)(uint32_t)v[i + 1] << 32) | (uint32_t)v[i]; };
-    PipeRec t;
-    t.valid = v[0]; t.L = v[1]; t.c0 = v[2]; t.rows = v[3]; t.pos0 = v[4]; t.spare = v[5];
+    PipeTask t;
+    t.valid = (v[0] >> 16) & 1; t.rows = v[0] & 0xffff; t.L = v[1]; t.c0 = v[2]; t.pos0 = v[3];
     t.kbase = reinterpret_cast<const char*>(ptr(6));
     t.qpart = reinterpret_cast<const char*>(ptr(8));
-    t.mod = reinterpret_cast<const uint8_t*>(ptr(10));
+    t.kbits = reinterpret_cast<const uint32_t*>(ptr(10));
     t.stat = reinterpret_cast<float*>(ptr(12));
     t.out_self = reinterpret_cast<float*>(ptr(14));
     return t;
 }
-__device__ __forceinline__ int rec_chunks(const PipeRec& t) { return (t.L + kPipeChunk - 1) / kPipeChunk; }
+// one word of a task's key modality bits, through the scalar cache
+__device__ __forceinline__ uint32_t load_bits(const uint32_t* at) {
+    uint32_t v;
+    asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(v) : "s"(at) : "memory");
+    return v;
+}
+// the modality bits of the 64 keys from position pos of the task's sequence on (bit i: key pos + i)
+__device__ __forceinline__ uint64_t load_bits64(const PipeTask& t, int pos) {
+    const uint32_t* const at = t.kbits - (t.c0 / kScoreSingleChunk) * (kScoreSingleChunk / 32) + pos / 32;
+    uint32_t w0, w1, w2;
+    asm volatile("s_load_dword %0, %3, 0x0\n\ts_load_dword %1, %3, 0x4\n\ts_load_dword %2, %3, 0x8\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(w0), "=&s"(w1), "=&s"(w2) : "s"(at) : "memory");
+    const int sh = pos % 32;
+    const uint64_t lo = ((uint64_t)w1 << 32) | w0, hi = ((uint64_t)w2 << 32) | w1;
+    return (uint64_t)(uint32_t)(lo >> sh) | ((uint64_t)(uint32_t)(hi >> sh) << 32);
+}
+__device__ __forceinline__ int rec_chunks(const PipeTask& t) { return (t.L + kPipeChunk - 1) / kPipeChunk; }
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -201,10 +243,6 @@ __device__ __forceinline__ void load_to_lds_16(const void* lane_addr, uint32_t l
     const uint64_t a = reinterpret_cast<uint64_t>(lane_addr);
     if constexpr (NT_HINT) asm volatile(CSP_DMA_ASM("global_load_lds_dwordx4", "%0, off", " nt") ::"v"(a), "s"(0), "s"(lds) : "memory", "m0");
     else asm volatile(CSP_DMA_ASM("global_load_lds_dwordx4", "%0, off", "") ::"v"(a), "s"(0), "s"(lds) : "memory", "m0");
-}
-// one byte per lane, zero-extended to the lane's dword
-__device__ __forceinline__ void load_to_lds_1(const void* base, uint32_t lane_off, uint32_t lds) {
-    asm volatile(CSP_DMA_ASM("global_load_lds_ubyte", "%1, %0", "") ::"s"(base), "v"(lane_off), "s"(lds) : "memory", "m0");
 }
 // 4 bytes per lane at agent scope (sc1): sees what other workgroups published with agent-scope stores
 __device__ __forceinline__ void load_to_lds_4_agent(const void* base, uint32_t lane_off, uint32_t lds) {
@@ -325,7 +363,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     constexpr int kQFrags = NQB * TG::NK;                               // 1 KiB query fragments
     constexpr int kQLoads = (kQFrags + kSWaves - 1) / kSWaves;          // ... each wavefront requests
     constexpr int kTileLoads = NT * TG::NLD;
-    constexpr int kQueryLoads = kQLoads + 1;                            // loads per wavefront of request_queries
+    constexpr int kQueryLoads = kQLoads;                                // loads per wavefront of request_queries
     // statistics: wavefront w merges rows w*RPW .. of the window part, lane = (row, chunk group)
     constexpr int RPW = NQ / kSWaves;                                   // rows per wavefront: 8 or 4
     constexpr int CG = kWave / RPW;                                     // chunk groups: lane takes chunks cg, cg + CG, ...
@@ -338,8 +376,6 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
 
     char* const q_lds = smem + SM::off_q;
     float* const stat_lds = reinterpret_cast<float*>(smem + SM::off_stat) + wave * (kPoll * 64);   // this wavefront's rows
-    uint32_t* const kmod_lds = reinterpret_cast<uint32_t*>(smem + SM::off_kmod) + wave * 64;
-    uint32_t* const wq_lds = reinterpret_cast<uint32_t*>(smem + SM::off_wq);
     float* const wmax = reinterpret_cast<float*>(smem + SM::off_wmax);
     float* const wsum = reinterpret_cast<float*>(smem + SM::off_wsum);
     _Float16* const fac = reinterpret_cast<_Float16*>(stat_lds);         // second half of the back stage: this wavefront's factor rows
@@ -361,7 +397,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     for (int i = tid; i < kFailWords; i += kSThreads) fail[i] = 0u;
     if (tid < 32) reinterpret_cast<uint32_t*>(smem + SM::off_zero)[tid] = 0u;
 
-    auto tile_j0 = [&](const PipeRec& t, int t4) { return t.c0 + (t4 * kSWaves + wave) * kTile; };
+    auto tile_j0 = [&](const PipeTask& t, int t4) { return t.c0 + (t4 * kSWaves + wave) * kTile; };
 
     // ---- requests (direct to LDS; every wavefront issues the same number on every path) --------
     // the tiles this wavefront takes of the task's chunk: instruction i of a tile covers rows
@@ -380,7 +416,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     // (loads first .. first + count - 1 of the kTileLoads, in the order tile, instruction)
     // ... of a chunk that lies inside its sequence: no branches, so that the requests stay where they
     // are written, between the arithmetic
-    auto request_keys_inside = [&](const PipeRec& t, KeyCursor& kc, int first, int count) {
+    auto request_keys_inside = [&](const PipeTask& t, KeyCursor& kc, int first, int count) {
 #pragma unroll
         for (int idx = 0; idx < kTileLoads; ++idx) {
             if (idx < first || idx >= first + count) continue;
@@ -391,7 +427,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         }
     };
     // ... of any chunk, all at once
-    auto request_keys_ragged = [&](const PipeRec& t) {
+    auto request_keys_ragged = [&](const PipeTask& t) {
         const int ln = opaque(lane);
         const int row_in = ln / TG::CPR;
 #pragma unroll
@@ -406,11 +442,10 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             }
         }
     };
-    auto chunk_inside = [&](const PipeRec& t) { return t.c0 + kPipeChunk <= t.L; };   // uniform
+    auto chunk_inside = [&](const PipeTask& t) { return t.c0 + kPipeChunk <= t.L; };   // uniform
     // the queries in MFMA operand order (fragment (mb, s) of lane l at ((mb*NK + s)*64 + l)*16; window
-    // rows past the part's last re-read it: finite logits that get weight 0), and the modality of
-    // the part's window rows
-    auto request_queries = [&](const PipeRec& t) {
+    // rows past the part's last re-read it: finite logits that get weight 0)
+    auto request_queries = [&](const PipeTask& t) {
         const int rows = t.rows;
         const char* qpart = t.qpart;
         const int ln = opaque(lane);
@@ -420,13 +455,9 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             const int row = min(mb * 32 + (ln & 31), rows - 1);
             load_to_lds_16<false>(qpart + s_ * 32, (uint32_t)((row * D + (ln >> 5) * 8) * 2), lds0 + SM::off_q + frag * 1024);
         }
-        // every wavefront requests the same 64 bytes into the same place (the load counts stay uniform)
-        const int pos = min(max(t.pos0 + (ln < rows ? ln : 0), 0), t.L - 1);
-        load_to_lds_1(t.mod, (uint32_t)pos, lds0 + SM::off_wq);
     };
-    // the first kPoll chunks of this lane's chunk group of the head's statistics, and the modality
-    // of this lane's keys (lanes 0-31: the wavefront's first tile, lanes 32-63: its second)
-    auto request_stats = [&](const PipeRec& t) {
+    // the first kPoll chunks of this lane's chunk group of the head's statistics
+    auto request_stats = [&](const PipeTask& t) {
         const int rows = t.rows, ncb = rec_chunks(t);
         const int ln = opaque(lane);
         const int row = wave * RPW + ln / CG, cg = ln % CG;
@@ -436,8 +467,6 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             const int ch = cg + CG * u;
             load_to_lds_4_agent(part, (uint32_t)((ch < ncb ? ch : ncb - 1) * kStatRows + (row < rows ? row : 0)) * 4u, lds0 + SM::off_stat + (wave * kPoll + u) * 256);
         }
-        const int j = tile_j0(t, ln >> 5) + (ln & 31);
-        load_to_lds_1(t.mod, (uint32_t)(j < t.L ? j : t.L - 1), lds0 + SM::off_kmod + wave * 256);
     };
 
     // ---- front stage: logits, statistics and the published log-sum-exp of the chunk ----------
@@ -450,9 +479,9 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     // On return pk holds the chunk's weights 2^15 * 2^(c*logit - wavefront maximum of the row) as fp16
     // pairs (pk[t4][mb][h]: accumulator registers 2h, 2h+1 of tile t4, query block mb), ref this
     // lane's row (my_row) of the references (maximum - 15) and win the modalities of the window rows.
-    auto front_a = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, const PipeRec& t, bool next_inside, auto&& next_keys, auto&& next_keys_ragged) {
+    auto front_a = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, const PipeTask& t, bool next_inside, auto&& next_keys, auto&& next_keys_ragged) {
         const int pos0 = t.pos0, c0 = t.c0;
-        win = wq_lds[my_row];
+        win = (uint32_t)((load_bits64(t, t.pos0) >> my_row) & 1u);   // (the window rows are keys of the sequence)
         // acc[t4][mb][v] = q_i . k_j, i = mb*32 + acc_row(v, half), j = tile_j0(t4) + lane%32
         f32x16 acc[NT][NQB];
         const f32x16 zero = {};   // (as the addend of an MFMA: a constant operand, no registers to clear)
@@ -563,7 +592,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         }
         CSP_TS(6);
     };
-    auto front_b = [&](const PipeRec& t) {
+    auto front_b = [&](const PipeTask& t) {
         const int rows = t.rows;
         {
             // log-sum-exp of the chunk per row (-inf when the row sees none of its keys): wavefront w
@@ -585,7 +614,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     // this wavefront's rows into the rows' log-sum-exp (LDS) and notes whether its wait ran out; after a
     // workgroup barrier back_b turns the waiting weights into scores and stores them, or returns false
     // (uniform) when some wavefront's wait ran out.
-    auto back_a = [&](const PipeRec& t, int64_t spin) {
+    auto back_a = [&](const PipeTask& t, int64_t spin) {
         const int rows = t.rows, n_chunks_b = rec_chunks(t);
         // (the few loads that the compiler sees, on the paths that are rarely taken: it waits for them
         // where their values are used, and with them for every load in flight)
@@ -653,7 +682,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             nl[st_row] = st_row < rows ? M + fast_log2(Lh) : __builtin_inff();   // rows past the window: weight 0
         }
     };
-    auto back_b = [&](const f16x2 (&pk)[NT][NQB][8], float ref, const WindowBits& win, const PipeRec& t) -> bool {
+    auto back_b = [&](const f16x2 (&pk)[NT][NQB][8], float ref, const WindowBits& win, const PipeTask& t) -> bool {
         bool all_ok = true;
 #pragma unroll
         for (int w = 0; w < kSWaves; ++w) all_ok = all_ok && flag[w] != 0;
@@ -702,7 +731,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             for (int t4 = 0; t4 < NT; ++t4) {
                 const float ct = (cs[t4][0] + cs[t4][1]) * kFactorUnshift;   // over the text window rows
                 const float cv = (cs[t4][2] + cs[t4][3]) * kFactorUnshift;   // over the visual window rows
-                const bool key_text = kmod_lds[t4 * 32 + lane] == 0;
+                const bool key_text = ((load_bits(t.kbits + t4 * kSWaves + wave) >> lane) & 1u) == 0;   // (lane < 32 here)
                 const int j = tile_j0(t, t4) + lane;
                 const bool ranked = j < rank_end;
                 if (j < t.L) {
@@ -726,7 +755,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     // record of this workgroup's task of step `it` (steps past the last: the record that is not valid)
     auto rec_of = [&](int it) { return p.table + (it >= 0 && it < p.n_iters ? min(it * nwg + (int)blockIdx.x, p.n_lin) : p.n_lin); };
     {
-        const PipeRec t0 = load_rec(rec_of(0));
+        const PipeTask t0 = load_rec(rec_of(0));
         request_queries(t0);
         request_keys_ragged(t0);
         wait_loads<0>();
@@ -747,7 +776,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         lds_barrier();   // the front task's queries have landed for every wavefront; the rows' log-sum-exps of task it - 2 are in LDS
         CSP_TS(1);
         {
-            const PipeRec tb = load_rec(rec_of(it - 2));
+            const PipeTask tb = load_rec(rec_of(it - 2));
             if (tb.valid && !back_b(pk, ref, win, tb) && tid == 0) {
                 fail[(it - 2) >> 5] |= 1u << ((it - 2) & 31);
                 atomicAdd(p.counters, 1);
@@ -755,11 +784,11 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         }
         CSP_TS(2);
         request_stats(load_rec(rec_of(it - 1)));
-        const PipeRec tn = load_rec(rec_of(it + 1));
+        const PipeTask tn = load_rec(rec_of(it + 1));
         KeyCursor kcn;
         auto keys_next = [&](int first, int count) { request_keys_inside(tn, kcn, first, count); };   // this wavefront is done with its tiles
         auto keys_next_ragged = [&]() { request_keys_ragged(tn); };
-        const PipeRec tf = load_rec(rec_of(it));
+        const PipeTask tf = load_rec(rec_of(it));
         CSP_TS(3);
         if (tf.valid) front_a(pk, ref, win, tf, chunk_inside(tn), keys_next, keys_next_ragged);
         else keys_next_ragged();
@@ -772,7 +801,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         wait_loads<kTileLoads + kQueryLoads>();   // the statistics and modalities of task it - 1 have landed
         CSP_TS(10);
         {
-            const PipeRec tm = load_rec(rec_of(it - 1));
+            const PipeTask tm = load_rec(rec_of(it - 1));
             if (tm.valid) back_a(tm, p.spin_ticks);
         }
         CSP_TS(11);
@@ -790,12 +819,12 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     lds_barrier();
     for (int it = 0; it < p.n_iters; ++it) {
         if (!((fail[it >> 5] >> (it & 31)) & 1u)) continue;   // uniform
-        const PipeRec t = load_rec(rec_of(it));
+        const PipeTask t = load_rec(rec_of(it));
         const int ncb = rec_chunks(t), own = t.c0 / kPipeChunk;
         auto no_keys = [&](int, int) {};
         auto no_keys_ragged = [&]() {};
         for (int k = 0; k < ncb; ++k) {
-            PipeRec ty = t;   // the chunks of a head part differ in their first key only
+            PipeTask ty = t;   // the chunks of a head part differ in their first key only
             ty.c0 = (k < ncb - 1 ? (k < own ? k : k + 1) : own) * kPipeChunk;
             lds_barrier();
             request_queries(ty);
@@ -821,7 +850,9 @@ hipError_t launch_single_typed(const ScoreParams& p, int n_wg, hipStream_t s) {
     // several tasks stream the same keys at the same time (GQA heads, window parts): plain loads that stay in L2
     auto k = p.G * p.vsplit > 1 ? score_single_kernel<D, NQB, true> : score_single_kernel<D, NQB, false>;
     const size_t n_stats = (size_t)p.B * p.H_q * p.vsplit * p.n_chunks * kStatRows;
-    const size_t n_setup = n_stats > (size_t)p.n_lin + 1 ? n_stats : (size_t)p.n_lin + 1;
+    const size_t n_bits = bits_rows(p) * bits_words(p) * 32;   // a thread per key
+    size_t n_setup = n_stats > (size_t)p.n_lin + 1 ? n_stats : (size_t)p.n_lin + 1;
+    if (n_bits > n_setup) n_setup = n_bits;
     hipLaunchKernelGGL(score_single_setup_kernel, dim3((unsigned)((n_setup + 255) / 256)), dim3(256), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -863,6 +894,7 @@ hipError_t launch_score_single(ScoreParams& p, int D, hipStream_t s) {
     // the task table follows the statistics in the workspace
     const size_t n_stats = (size_t)p.B * p.H_q * p.vsplit * p.n_chunks * kStatRows;
     p.table = reinterpret_cast<PipeRec*>(reinterpret_cast<char*>(p.part) + ((n_stats * sizeof(float) + 15) & ~(size_t)15));
+    p.modbits = reinterpret_cast<uint32_t*>(p.table + p.n_lin + 1);
     p.cross_delta = (p.gsplit > 1 ? p.slice_cross - p.slice_self : p.score_cross - p.score_self);
     p.D = D;
     const int rows = p.O < kStatRows ? p.O : kStatRows;

@@ -51,18 +51,20 @@ def test_workspace_sizes(P):
     # 128 keys at this size (2*8*32 chunks * 64 rows * 2 floats) against one float per (head, 512-key
     # chunk, row) of the single-read kernel
     assert P.csp_score_workspace_bytes(d) == 16 + 2 * 8 * 32 * 64 * 2 * 4
-    # benchmark shape: the single-read statistics (32 chunks of 512 keys) and its task table (a 64-byte
-    # record per (sequence, head, window part, chunk), and one more) are more than the two-pass
-    # statistics (4 chunks of 4096 keys, two floats each)
+    # benchmark shape: the single-read statistics (32 chunks of 512 keys), its task table (a 64-byte
+    # record per (sequence, head, window part, chunk), and one more) and the keys' modality as bits (a
+    # word per 32 keys of every (sequence, selection group)) are more than the two-pass statistics
+    # (4 chunks of 4096 keys, two floats each)
     L = 16384
     big = dict(B=4, H_q=32, H_kv=32, max_seqlen=L, cu_seqlens_host=[0, L, 2 * L, 3 * L, 4 * L], budget_T_host=[L // 2] * 4,
                k_strides=(128, 4 * L * 128), v_strides=(128, 4 * L * 128))
     table = (4 * 32 * 32 + 1) * 64
-    assert P.csp_score_workspace_bytes(_desc(P, **big)) == 16 + 4 * 32 * 32 * 64 * 4 + table
+    bits = lambda groups: (4 * groups * 32 * 16 + 2) * 4
+    assert P.csp_score_workspace_bytes(_desc(P, **big)) == 16 + 4 * 32 * 32 * 64 * 4 + table + bits(32)
     # all heads in one selection group: one score array pair per head on top of that
-    assert P.csp_score_workspace_bytes(_desc(P, sel_group=32, **big)) == 16 + 4 * 32 * 32 * 64 * 4 + table + 2 * 32 * 4 * L * 4
+    assert P.csp_score_workspace_bytes(_desc(P, sel_group=32, **big)) == 16 + 4 * 32 * 32 * 64 * 4 + table + bits(1) + 2 * 32 * 4 * L * 4
     # a window of 128 rows is scored in two parts of 64: statistics and score arrays per part
-    assert P.csp_score_workspace_bytes(_desc(P, window_O=128, recent_R=128, **big)) == 16 + 4 * 32 * 2 * 32 * 64 * 4 + (4 * 32 * 2 * 32 + 1) * 64 + 2 * 2 * 32 * 4 * L * 4
+    assert P.csp_score_workspace_bytes(_desc(P, window_O=128, recent_R=128, **big)) == 16 + 4 * 32 * 2 * 32 * 64 * 4 + (4 * 32 * 2 * 32 + 1) * 64 + bits(32) + 2 * 2 * 32 * 4 * L * 4
     # fp32 keeps the two passes
     assert P.csp_score_workspace_bytes(_desc(P, dtype="f32", **big)) == 16 + 4 * 32 * 4 * 64 * 2 * 4
     assert P.csp_select_workspace_bytes(d) == 0
