@@ -29,8 +29,13 @@ constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kBins = 2048;
 constexpr uint32_t kNone = 0xffffffffu;  // "not a candidate": no finite non-negative float
 
+// The first pass sees every key, and scores crowd into few digits (a handful of exponents): lanes of a
+// wavefront that hit the same counter are served one after the other.  It spreads the lanes over
+// kHistCopies copies of the histograms (lane % kHistCopies); the later passes see few keys and use copy 0.
+constexpr int kHistCopies = 8;
+
 struct SelShared {
-    uint32_t hist[2][kBins];
+    uint32_t hist[kHistCopies][2][kBins];
     uint64_t wsum[kSelWaves];
     uint32_t has[2];
     uint32_t digit[2], rem[2];
@@ -136,7 +141,9 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         const int nbits = pass == 2 ? 10 : 11;
         const int prev_shift = pass == 1 ? 21 : 10;  // bits above the current digit
         const uint32_t dmask = (1u << nbits) - 1u;
-        for (int i = tid; i < 2 * kBins; i += kSelThreads) (&sh.hist[0][0])[i] = 0u;
+        const int copies = pass == 0 ? kHistCopies : 1;
+        for (int i = tid; i < copies * 2 * kBins; i += kSelThreads) (&sh.hist[0][0][0])[i] = 0u;
+        uint32_t (*const my_hist)[kBins] = sh.hist[pass == 0 ? (tid & (kHistCopies - 1)) : 0];
         __syncthreads();
 #pragma unroll 1
         for (int sb = 0; sb < n_super; ++sb) {
@@ -148,13 +155,13 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
                     for (int r = 0; r < 2; ++r) {
                         const uint32_t a = pat(i, r);
                         if (a != kNone && !none[r] && (pass == 0 || (a >> prev_shift) == prefix[r]))
-                            atomicAdd(&sh.hist[r][(a >> shift) & dmask], 1u);
+                            atomicAdd(&my_hist[r][(a >> shift) & dmask], 1u);
                     }
                 } else {
                     const int r = (in_cross >> i) & 1u;  // the key's only region
                     const uint32_t a = ka[i];
                     if (a != kNone && !(r ? none[1] : none[0]) && (pass == 0 || (a >> prev_shift) == (r ? prefix[1] : prefix[0])))
-                        atomicAdd(&sh.hist[r][(a >> shift) & dmask], 1u);
+                        atomicAdd(&my_hist[r][(a >> shift) & dmask], 1u);
                 }
             }
         }
@@ -163,8 +170,10 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         const int nb = 1 << nbits;
         const int hi = nb - 1 - 2 * tid;
         uint32_t c_hi[2] = {0u, 0u}, c_lo[2] = {0u, 0u};
-        if (hi >= 0) { c_hi[0] = sh.hist[0][hi]; c_hi[1] = sh.hist[1][hi]; }
-        if (hi >= 1) { c_lo[0] = sh.hist[0][hi - 1]; c_lo[1] = sh.hist[1][hi - 1]; }
+        for (int cp = 0; cp < copies; ++cp) {
+            if (hi >= 0) { c_hi[0] += sh.hist[cp][0][hi]; c_hi[1] += sh.hist[cp][1][hi]; }
+            if (hi >= 1) { c_lo[0] += sh.hist[cp][0][hi - 1]; c_lo[1] += sh.hist[cp][1][hi - 1]; }
+        }
         uint64_t excl, total;
         block_scan_pair((uint64_t)(c_hi[0] + c_lo[0]) | ((uint64_t)(c_hi[1] + c_lo[1]) << 32), sh.wsum, excl, total);
         if (pass == 0) {
@@ -283,7 +292,8 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
 
 template <int ITEMS>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
-    __shared__ SelShared sh;
+    extern __shared__ __align__(16) char sel_smem[];
+    SelShared& sh = *reinterpret_cast<SelShared*>(sel_smem);
     const int sg = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x;
     SelCtx c;
@@ -326,10 +336,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
 hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s) {
     const dim3 grid(p.H_sel, p.B), block(kSelThreads);
     const int items = (max_seqlen + kSelThreads - 1) / kSelThreads;
-    if (items <= 4) hipLaunchKernelGGL(select_kernel<4>, grid, block, 0, s, p);
-    else if (items <= 8) hipLaunchKernelGGL(select_kernel<8>, grid, block, 0, s, p);
-    else hipLaunchKernelGGL(select_kernel<16>, grid, block, 0, s, p);  // longer than 16K keys: several super-blocks
-    return hipGetLastError();
+    auto launch = [&](auto kernel) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(SelShared));
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kernel, grid, block, sizeof(SelShared), s, p);
+        return hipGetLastError();
+    };
+    if (items <= 4) return launch(select_kernel<4>);
+    if (items <= 8) return launch(select_kernel<8>);
+    return launch(select_kernel<16>);  // longer than 16K keys: several super-blocks
 }
 
 }  // namespace csp
