@@ -350,12 +350,23 @@ typedef uint32_t WindowBits;
 #else
 #define CSP_TS(slot) do { } while (0)
 #endif
+// ... -DCSP_SINGLE_TIMING_ALL: every workgroup records the constant-rate clock (10 ns ticks) at four
+// points of every step (4 slots per step, 32 steps per workgroup), in the same place.
+#ifdef CSP_SINGLE_TIMING_ALL
+#define CSP_TSA(k) do { if (threadIdx.x == 0 && tsa_it >= 0 && tsa_it < 32) tsa_buf[((long long)blockIdx.x * 32 + tsa_it) * 4 + (k)] = wall_clock64(); } while (0)
+#else
+#define CSP_TSA(k) do { } while (0)
+#endif
 
 template <int D, int NQB, bool REUSED>
 __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams p) {
 #ifdef CSP_SINGLE_TIMING
-    long long* const ts_buf = reinterpret_cast<long long*>(p.part + (size_t)p.B * p.H_q * p.vsplit * p.n_chunks * kStatRows);
+    long long* const ts_buf = reinterpret_cast<long long*>(p.modbits + bits_rows(p) * bits_words(p) + 2);
     int ts_it = -1;
+#endif
+#ifdef CSP_SINGLE_TIMING_ALL
+    long long* const tsa_buf = reinterpret_cast<long long*>(p.modbits + bits_rows(p) * bits_words(p) + 2);
+    int tsa_it = -1;
 #endif
     using TG = TileGeom<D>;
     using SM = PipeSmem<D, NQB>;
@@ -516,6 +527,8 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             const int lm = opaque(lane);
 #pragma unroll
             for (int t4 = 0; t4 < NT; ++t4) {
+                // (tile by tile: of the last chunk of a long sequence only the tiles of the window itself need it)
+                if (tile_j0(t, t4) + kTile <= (p.causal ? pos0 : t.L)) continue;   // uniform
                 const int j = tile_j0(t, t4) + (lm & 31);
 #pragma unroll
                 for (int mb = 0; mb < NQB; ++mb)
@@ -772,9 +785,13 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
 #ifdef CSP_SINGLE_TIMING
         ts_it = it;
 #endif
+#ifdef CSP_SINGLE_TIMING_ALL
+        tsa_it = it;
+#endif
         CSP_TS(0);
         lds_barrier();   // the front task's queries have landed for every wavefront; the rows' log-sum-exps of task it - 2 are in LDS
         CSP_TS(1);
+        CSP_TSA(0);
         {
             const PipeTask tb = load_rec(rec_of(it - 2));
             if (tb.valid && !back_b(pk, ref, win, tb) && tid == 0) {
@@ -798,13 +815,16 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         request_queries(tn);
         if (tf.valid) front_b(tf);
         CSP_TS(9);
+        CSP_TSA(3);
         wait_loads<kTileLoads + kQueryLoads>();   // the statistics and modalities of task it - 1 have landed
         CSP_TS(10);
+        CSP_TSA(1);
         {
             const PipeTask tm = load_rec(rec_of(it - 1));
             if (tm.valid) back_a(tm, p.spin_ticks);
         }
         CSP_TS(11);
+        CSP_TSA(2);
         wait_loads<0>();   // the next task's keys and queries (this wavefront's) have landed
         CSP_TS(12);
         CSP_TS(13);
