@@ -272,16 +272,7 @@ __device__ __forceinline__ int opaque(int x) {
     return x;
 }
 
-// ---- reduce-scatter over the 32 lanes of a half-wavefront, in the vector ALU ------------------
-// x[r], r < N, holds this lane's value for register index r; on return lane l holds in x[0] the
-// reduction over the 32 lanes of its half for r = l % N (N == 16: lanes l and l ^ 16 both).
-// Level by level the lanes l and l ^ MASK share out the registers they still hold: the lane whose
-// selector bit is set keeps the upper half, its partner the lower, and each adds the other's copy
-// of what it keeps.  The masks 16, 8, 7, 2, 1 are independent, each contains its selector bit
-// (16, 8, 4, 2, 1) and none touches the selector of an earlier level, so after the five levels
-// every lane has seen all 32; each exchange is one lane-crossing move that the data-parallel
-// primitives do without LDS: a swap of 16-lane rows between two registers, a rotation by 8 within a
-// row, a mirror of 8 lanes, two permutations within 4.
+// ---- lane-crossing reductions in the vector ALU (data-parallel primitives, no LDS) --------------
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 template <int CTRL>
 __device__ __forceinline__ float lane_xchg(float x) {
@@ -291,41 +282,6 @@ __device__ __forceinline__ float lane_xchg(float x) {
 }
 template <bool MAX>
 __device__ __forceinline__ float red_op(float a, float b) { return MAX ? fmaxf(a, b) : a + b; }
-template <int N, int W, int CTRL, int SEL, bool MAX>
-__device__ __forceinline__ void rs_level(float (&x)[N], int lane) {
-    const bool up = (lane & SEL) != 0;
-#pragma unroll
-    for (int k = 0; k < W; ++k) {
-        const float lo = red_op<MAX>(x[k], lane_xchg<CTRL>(x[k]));
-        const float hi = red_op<MAX>(x[k + W], lane_xchg<CTRL>(x[k + W]));
-        x[k] = up ? hi : lo;
-    }
-}
-template <int N, bool MAX>
-__device__ __forceinline__ float reduce_scatter_valu(float (&x)[N], int lane) {
-    static_assert(N == 32 || N == 16, "32 or 16 values per lane");
-    if constexpr (N == 32) {
-        // lanes l and l ^ 16: rows of 16 lanes swapped between the two registers of a pair
-#pragma unroll
-        for (int k = 0; k < 16; ++k) {
-            const u32x2 r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, x[k]), __builtin_bit_cast(unsigned, x[k + 16]), false, false);
-            const unsigned r0 = r[0], r1 = r[1];  // copies: a bit cast of a vector element reads element 0
-            x[k] = red_op<MAX>(__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1));
-        }
-    }
-    rs_level<N, 8, 0x128, 8, MAX>(x, lane);   // row_ror:8
-    rs_level<N, 4, 0x141, 4, MAX>(x, lane);   // row_half_mirror: l ^ 7
-    rs_level<N, 2, 0x4E, 2, MAX>(x, lane);    // quad_perm [2,3,0,1]
-    rs_level<N, 1, 0xB1, 1, MAX>(x, lane);    // quad_perm [1,0,3,2]
-    float r = x[0];
-    if constexpr (N == 16) {
-        const u32x2 s = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, r), __builtin_bit_cast(unsigned, r), false, false);
-        const unsigned s0 = s[0], s1 = s[1];
-        r = red_op<MAX>(__builtin_bit_cast(float, s0), __builtin_bit_cast(float, s1));
-    }
-    return r;
-}
-
 // All-reduce over aligned groups of GROUP = 8 or 16 lanes: every lane ends up with the same value
 // (the two lanes of an exchange compute a op b and b op a).
 template <int GROUP, bool MAX>
@@ -338,15 +294,23 @@ __device__ __forceinline__ float group_allreduce(float x) {
     return x;
 }
 
+// All-reduce over the two lanes l and l ^ 32.
+template <bool MAX>
+__device__ __forceinline__ float halves_allreduce(float x) {
+    const u32x2 s = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, x), __builtin_bit_cast(unsigned, x), false, false);
+    const unsigned s0 = s[0], s1 = s[1];   // copies: a bit cast of a vector element reads element 0
+    return red_op<MAX>(__builtin_bit_cast(float, s0), __builtin_bit_cast(float, s1));
+}
+
 template <bool V> struct Interleaved { static constexpr bool value = V; };
 
 // Modality of this lane's window row (my_row) of a task, carried from its front stage to its back stage.
 typedef uint32_t WindowBits;
 
-// Development aid: -DCSP_SINGLE_TIMING makes workgroup 0 record the shader clock at the phase
-// boundaries of every step behind the statistics in the workspace (16 slots per step).
+// Development aid: -DCSP_SINGLE_TIMING=w makes wavefront w of workgroup 0 record the shader clock at the
+// phase boundaries of every step behind the modality bits in the workspace (16 slots per step).
 #ifdef CSP_SINGLE_TIMING
-#define CSP_TS(slot) do { if (blockIdx.x == 0 && threadIdx.x == 0 && ts_it >= 0 && ts_it < 64) ts_buf[ts_it * 16 + (slot)] = clock64(); } while (0)
+#define CSP_TS(slot) do { if (blockIdx.x == 0 && threadIdx.x == (CSP_SINGLE_TIMING) * 64 && ts_it >= 0 && ts_it < 64) ts_buf[ts_it * 16 + (slot)] = clock64(); } while (0)
 #else
 #define CSP_TS(slot) do { } while (0)
 #endif
@@ -374,6 +338,11 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     constexpr int kQFrags = NQB * TG::NK;                               // 1 KiB query fragments
     constexpr int kQLoads = (kQFrags + kSWaves - 1) / kSWaves;          // ... each wavefront requests
     constexpr int kTileLoads = NT * TG::NLD;
+        // requests for the next task's keys: a quarter when the MFMAs of the first tile are done (into that tile's
+    // buffer), the rest between the exponentials
+    // (keys that several tasks stream at the same time come from the L2: no head start, and the back stage first)
+    constexpr int kEarlyLoads = REUSED ? 0 : kTileLoads / 4, kLateLoads = kTileLoads - kEarlyLoads;
+    static_assert(kEarlyLoads <= TG::NLD, "the early requests go to the first tile");
     constexpr int kQueryLoads = kQLoads;                                // loads per wavefront of request_queries
     // statistics: wavefront w merges rows w*RPW .. of the window part, lane = (row, chunk group)
     constexpr int RPW = NQ / kSWaves;                                   // rows per wavefront: 8 or 4
@@ -396,7 +365,8 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     auto tile_ptr = [&](int t4) { return smem + (wave * NT + t4) * TG::TILE_LDS; };
     const uint32_t lds0 = lds_addr(smem);
     auto tile_lds = [&](int t4) { return lds0 + (uint32_t)((wave * NT + t4) * TG::TILE_LDS); };
-    // row of the window this lane ends up with after a reduce_scatter
+    // row of the window this lane looks after in the back stage: its reference, its modality, its factor
+    // (a part of 32 rows: lanes l and l ^ 16 the same row)
     const int my_row = ((lane & (N - 1)) >> 4) * 32 + acc_row(lane & 15, half);
     // row and chunk group whose statistics this lane merges
     const int st_row = wave * RPW + lane / CG, st_cg = lane % CG;
@@ -437,8 +407,8 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             kc.at += row_step;
         }
     };
-    // ... of any chunk, all at once
-    auto request_keys_ragged = [&](const PipeTask& t) {
+    // ... of any chunk (the same loads, the same order), in one go
+    auto request_keys_ragged = [&](const PipeTask& t, int first, int count) {
         const int ln = opaque(lane);
         const int row_in = ln / TG::CPR;
 #pragma unroll
@@ -446,6 +416,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
             const int j0 = tile_j0(t, t4);
 #pragma unroll
             for (int i = 0; i < TG::NLD; ++i) {
+                if (t4 * TG::NLD + i < first || t4 * TG::NLD + i >= first + count) continue;
                 const int first_row = j0 + i * TG::RPI, left = t.L - 1 - first_row;   // uniform: rows of the sequence after the first
                 const uint32_t piece = (uint32_t)(((ln % TG::CPR) ^ TG::key(i * TG::RPI + row_in)) * 16);
                 const char* const at = t.kbase + (int64_t)(left > 0 ? first_row : t.L - 1) * tok_bytes;
@@ -490,10 +461,12 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     // On return pk holds the chunk's weights 2^15 * 2^(c*logit - wavefront maximum of the row) as fp16
     // pairs (pk[t4][mb][h]: accumulator registers 2h, 2h+1 of tile t4, query block mb), ref this
     // lane's row (my_row) of the references (maximum - 15) and win the modalities of the window rows.
-    auto front_a = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, const PipeTask& t, bool next_inside, auto&& next_keys, auto&& next_keys_ragged) {
+    auto front_a = [&](f16x2 (&pk)[NT][NQB][8], float& ref, WindowBits& win, const PipeTask& t, bool next_inside, auto&& next_keys, auto&& next_keys_ragged, auto&& first_tile_done, auto&& after_logits) {
         const int pos0 = t.pos0, c0 = t.c0;
-        win = (uint32_t)((load_bits64(t, t.pos0) >> my_row) & 1u);   // (the window rows are keys of the sequence)
-        // acc[t4][mb][v] = q_i . k_j, i = mb*32 + acc_row(v, half), j = tile_j0(t4) + lane%32
+        const WindowBits win_new = (uint32_t)((load_bits64(t, t.pos0) >> my_row) & 1u);   // (the window rows are keys of the sequence)
+        // acc[t4][mb][v] = k_j . q_i, j = tile_j0(t4) + acc_row(v, half), i = mb*32 + lane%32: window rows
+        // on the lane axis, so that a row's maximum is found within a lane (and its other half) and
+        // its sum by an MFMA whose contraction runs over the registers, i.e. over the keys
         f32x16 acc[NT][NQB];
         const f32x16 zero = {};   // (as the addend of an MFMA: a constant operand, no registers to clear)
         // the key operands of contraction step s+1 are requested before the MFMAs of step s are issued
@@ -502,107 +475,154 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         // piece (s*2 + half) ^ key(r) of row r: the steps differ by an XOR of the byte offset with s*32
         const int ln = opaque(lane);
         const int kaddr0 = (ln & 31) * TG::ROW_BYTES + (((ln >> 5) ^ TG::key(ln & 31)) * 16);
-        bf16x8 kf[2][NT];
-        auto fetch_keys = [&](int s_, int b2) {
+        if constexpr (!REUSED) {
+            // tile by tile: the first tile's buffer is free for the next task's keys while the second tile's
+            // MFMAs run (the queries are read from LDS once per tile)
+            bf16x8 kf[2];
+    #pragma unroll
+            for (int t4 = 0; t4 < NT; ++t4) {
+                kf[0] = *reinterpret_cast<const bf16x8*>(tile_ptr(t4) + kaddr0);
+    #pragma unroll
+                for (int s_ = 0; s_ < TG::NK; ++s_) {
+                    bf16x8 qa[NQB];
+    #pragma unroll
+                    for (int mb = 0; mb < NQB; ++mb) qa[mb] = *reinterpret_cast<const bf16x8*>(q_lds + ((mb * TG::NK + s_) * 64 + lane) * 16);
+                    if (s_ + 1 < TG::NK) kf[(s_ + 1) & 1] = *reinterpret_cast<const bf16x8*>(tile_ptr(t4) + (kaddr0 ^ ((s_ + 1) * 32)));
+                    __builtin_amdgcn_sched_barrier(0);
+    #pragma unroll
+                    for (int mb = 0; mb < NQB; ++mb) acc[t4][mb] = mma(kf[s_ & 1], qa[mb], s_ == 0 ? zero : acc[t4][mb]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (t4 == 0) first_tile_done();
+            }
+        } else {
+            // keys that several tasks stream at the same time come from the L2: no hurry to ask for the next
+            // ones, and the queries are read from LDS once per contraction step for both tiles
+            bf16x8 kf[2][NT];
+            auto fetch_keys = [&](int s_, int b2) {
 #pragma unroll
-            for (int t4 = 0; t4 < NT; ++t4) kf[b2][t4] = *reinterpret_cast<const bf16x8*>(tile_ptr(t4) + (kaddr0 ^ (s_ * 32)));
-        };
-        fetch_keys(0, 0);
+                for (int t4 = 0; t4 < NT; ++t4) kf[b2][t4] = *reinterpret_cast<const bf16x8*>(tile_ptr(t4) + (kaddr0 ^ (s_ * 32)));
+            };
+            fetch_keys(0, 0);
 #pragma unroll
-        for (int s_ = 0; s_ < TG::NK; ++s_) {
-            bf16x8 qa[NQB];
+            for (int s_ = 0; s_ < TG::NK; ++s_) {
+                bf16x8 qa[NQB];
 #pragma unroll
-            for (int mb = 0; mb < NQB; ++mb) qa[mb] = *reinterpret_cast<const bf16x8*>(q_lds + ((mb * TG::NK + s_) * 64 + lane) * 16);
-            if (s_ + 1 < TG::NK) fetch_keys(s_ + 1, (s_ + 1) & 1);
-            __builtin_amdgcn_sched_barrier(0);
+                for (int mb = 0; mb < NQB; ++mb) qa[mb] = *reinterpret_cast<const bf16x8*>(q_lds + ((mb * TG::NK + s_) * 64 + lane) * 16);
+                if (s_ + 1 < TG::NK) fetch_keys(s_ + 1, (s_ + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int t4 = 0; t4 < NT; ++t4)
+                for (int t4 = 0; t4 < NT; ++t4)
 #pragma unroll
-                for (int mb = 0; mb < NQB; ++mb) acc[t4][mb] = mma(qa[mb], kf[s_ & 1][t4], s_ == 0 ? zero : acc[t4][mb]);
-            __builtin_amdgcn_sched_barrier(0);
+                    for (int mb = 0; mb < NQB; ++mb) acc[t4][mb] = mma(kf[s_ & 1][t4], qa[mb], s_ == 0 ? zero : acc[t4][mb]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            first_tile_done();
         }
         CSP_TS(4);
+        // Then the back stage of the task two steps back (whose registers pk, ref and win are about to be
+        // reused).  (The requests for the next task's keys start as early as the single tile buffer allows,
+        // with first_tile_done(): together the workgroups ask for more in a step than the memory delivers in
+        // the part of it that is left after the logits.  More than a quarter of them in one go holds up the
+        // wavefront at the memory pipeline for longer than the head start is worth.)
+        after_logits();
         // keys past the end, and keys a row may not see (causal tail)
         if (c0 + kPipeChunk > (p.causal ? pos0 : t.L)) {
-            const int lm = opaque(lane);
 #pragma unroll
             for (int t4 = 0; t4 < NT; ++t4) {
                 // (tile by tile: of the last chunk of a long sequence only the tiles of the window itself need it)
                 if (tile_j0(t, t4) + kTile <= (p.causal ? pos0 : t.L)) continue;   // uniform
-                const int j = tile_j0(t, t4) + (lm & 31);
+                const int lm = opaque(lane);   // (here: what follows stays behind the branch)
 #pragma unroll
-                for (int mb = 0; mb < NQB; ++mb)
+                for (int mb = 0; mb < NQB; ++mb) {
+                    const int i = mb * 32 + (lm & 31);
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int i = mb * 32 + acc_row(v, lm >> 5);
+                        const int j = tile_j0(t, t4) + acc_row(v, lm >> 5);
                         const bool ok = j < t.L && (!p.causal || j <= pos0 + i);
                         acc[t4][mb][v] = ok ? acc[t4][mb][v] : NEG_INF;
                     }
+                }
             }
         }
-        // row maxima over this wavefront's keys: the reference of its exponentials
+        // row maxima over this wavefront's keys: the reference of its exponentials.  A lane has 16
+        // keys of each tile for its row, the lane 32 further on the other 16
         float* const wm = wmax + wave * NQ;
-        const float* const wm_lane = wm + opaque(half) * 4;   // this lane's rows: blocks of 4 at +8*k
-        {
-            float rm[N];
+        float refs[NQB];
 #pragma unroll
-            for (int mb = 0; mb < NQB; ++mb)
+        for (int mb = 0; mb < NQB; ++mb) {
+            float m = acc[0][mb][0];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    float m = acc[0][mb][v];
+            for (int t4 = 0; t4 < NT; ++t4)
 #pragma unroll
-                    for (int t4 = 1; t4 < NT; ++t4) m = fmaxf(m, acc[t4][mb][v]);
-                    rm[mb * 16 + v] = m;
-                }
-            const float m = reduce_scatter_valu<N, true>(rm, lane) * c;
-            ref = (m == NEG_INF ? 0.f : m) - kWeightShift;   // a row that sees none of these keys: every weight is 0 anyway
-            wm[my_row] = ref;
+                for (int v = (t4 == 0 ? 1 : 0); v < 16; ++v) m = fmaxf(m, acc[t4][mb][v]);
+            m = halves_allreduce<true>(m) * c;
+            refs[mb] = (m == NEG_INF ? 0.f : m) - kWeightShift;   // a row that sees none of these keys: every weight is 0 anyway
+            wm[mb * 32 + (lane & 31)] = refs[mb];                 // (both halves write the same value)
         }
         CSP_TS(5);
-        wave_lds_sync();
-        // weights in place of the logits, their row sums, and the fp16 copies that wait for the head's
-        // statistics (half the registers; 11 bits are within the tolerance, and the scale keeps small
-        // weights normal): a pair of accumulator registers at a time, so that few fp32 weights are live
+        // weights in place of the logits, as fp16 (half the registers; 11 bits are within the tolerance,
+        // and the scale keeps small weights normal).  Per block of 32 keys x 32 rows: the row sums are an
+        // MFMA of the block with a matrix of ones (the contraction runs over the block's keys), and an
+        // MFMA of the block with a permutation matrix hands every weight, unchanged, to the lane of its
+        // key (the layout in which the back stage contracts over the window rows): what the vector ALU
+        // does per weight is one FMA, one exponential and two conversions.
         auto weights = [&](auto interleave) {
-            float rs[N];
+            constexpr int kIters = NQB * NT * 4;
+            const int lw = opaque(lane);
+            f16x8 ones, perm_lo, perm_hi;   // perm_lo/hi[e]: accumulator register e (8 + e) of this half is key lane%32 of the tile
 #pragma unroll
-            for (int mb = 0; mb < NQB; ++mb)
+            for (int e = 0; e < 8; ++e) {
+                ones[e] = (_Float16)1.f;
+                perm_lo[e] = acc_row(e, lw >> 5) == (lw & 31) ? (_Float16)1.f : (_Float16)0.f;
+                perm_hi[e] = acc_row(8 + e, lw >> 5) == (lw & 31) ? (_Float16)1.f : (_Float16)0.f;
+            }
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    constexpr int kPer = kTileLoads / (NQB * 4);
-                    static_assert(kPer * NQB * 4 == kTileLoads, "the requests divide evenly over the iterations");
-                    if constexpr (decltype(interleave)::value) {
-                        __builtin_amdgcn_sched_barrier(0);   // (here, not all of them ahead of the arithmetic)
-                        next_keys((mb * 4 + v4) * kPer, kPer);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    const float4 w = *reinterpret_cast<const float4*>(wm_lane + mb * 32 + v4 * 8);
-                    const float ms[4] = {w.x, w.y, w.z, w.w};
+            for (int mb = 0; mb < NQB; ++mb) {
+                f32x16 sums;
 #pragma unroll
-                    for (int u = 0; u < 4; u += 2) {
-                        const int v = v4 * 4 + u;
-                        float sum0 = 0.f, sum1 = 0.f;
+                for (int t4 = 0; t4 < NT; ++t4) {
+                    f16x2 wt[8];
 #pragma unroll
-                        for (int t4 = 0; t4 < NT; ++t4) {
-                            const float e0 = fast_exp2(fmaf(acc[t4][mb][v], c, -ms[u]));
-                            const float e1 = fast_exp2(fmaf(acc[t4][mb][v + 1], c, -ms[u + 1]));
-                            sum0 += e0;
-                            sum1 += e1;
-                            const f32x2 two = {e0, e1};
-                            pk[t4][mb][v >> 1] = __builtin_convertvector(two, f16x2);
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        if constexpr (decltype(interleave)::value) {
+                            const int idx = (mb * NT + t4) * 4 + v4;
+                            const int first = kEarlyLoads + idx * kLateLoads / kIters, count = kEarlyLoads + (idx + 1) * kLateLoads / kIters - first;
+                            __builtin_amdgcn_sched_barrier(0);   // (here, not all of them ahead of the arithmetic)
+                            next_keys(first, count);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
-                        rs[mb * 16 + v] = sum0;
-                        rs[mb * 16 + v + 1] = sum1;
+#pragma unroll
+                        for (int u = 0; u < 4; u += 2) {
+                            const int v = v4 * 4 + u;
+                            const f32x2 two = {fast_exp2(fmaf(acc[t4][mb][v], c, -refs[mb])), fast_exp2(fmaf(acc[t4][mb][v + 1], c, -refs[mb]))};
+                            wt[v >> 1] = __builtin_convertvector(two, f16x2);
+                        }
+                    }
+                    const f16x8 w_lo = __builtin_shufflevector(__builtin_shufflevector(wt[0], wt[1], 0, 1, 2, 3), __builtin_shufflevector(wt[2], wt[3], 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+                    const f16x8 w_hi = __builtin_shufflevector(__builtin_shufflevector(wt[4], wt[5], 0, 1, 2, 3), __builtin_shufflevector(wt[6], wt[7], 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
+                    sums = mma_f16(ones, w_lo, t4 == 0 ? zero : sums);
+                    sums = mma_f16(ones, w_hi, sums);
+                    f32x16 d = mma_f16(w_lo, perm_lo, zero);
+                    d = mma_f16(w_hi, perm_hi, d);
+#pragma unroll
+                    for (int h = 0; h < 8; ++h) {
+                        const f32x2 two = {d[2 * h], d[2 * h + 1]};
+                        pk[t4][mb][h] = __builtin_convertvector(two, f16x2);
                     }
                 }
-            wsum[wave * NQ + my_row] = reduce_scatter_valu<N, false>(rs, lane);
+                wsum[wave * NQ + mb * 32 + (lane & 31)] = sums[0];   // (every row of the product is the same)
+            }
         };
         if (next_inside) {
             weights(Interleaved<true>{});
         } else {
-            next_keys_ragged();
+            next_keys_ragged(kEarlyLoads, kLateLoads);
             weights(Interleaved<false>{});
         }
+        wave_lds_sync();
+        ref = wm[my_row];
+        win = win_new;
         CSP_TS(6);
     };
     auto front_b = [&](const PipeTask& t) {
@@ -770,7 +790,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     {
         const PipeTask t0 = load_rec(rec_of(0));
         request_queries(t0);
-        request_keys_ragged(t0);
+        request_keys_ragged(t0, 0, kTileLoads);
         wait_loads<0>();
     }
     // One step, for the tasks it, it - 1 and it - 2 of this workgroup: the scores of task it - 2 from
@@ -792,23 +812,38 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         lds_barrier();   // the front task's queries have landed for every wavefront; the rows' log-sum-exps of task it - 2 are in LDS
         CSP_TS(1);
         CSP_TSA(0);
-        {
+        const PipeTask tn = load_rec(rec_of(it + 1));
+        const bool next_inside = chunk_inside(tn);
+        KeyCursor kcn;
+        auto keys_next = [&](int first, int count) { request_keys_inside(tn, kcn, first, count); };
+        auto keys_next_ragged = [&](int first, int count) { request_keys_ragged(tn, first, count); };
+        auto first_tile_done = [&]() {
+            if (next_inside) keys_next(0, kEarlyLoads);
+            else keys_next_ragged(0, kEarlyLoads);
+        };
+        auto after_logits = [&]() {
+            CSP_TS(2);
             const PipeTask tb = load_rec(rec_of(it - 2));
             if (tb.valid && !back_b(pk, ref, win, tb) && tid == 0) {
                 fail[(it - 2) >> 5] |= 1u << ((it - 2) & 31);
                 atomicAdd(p.counters, 1);
             }
-        }
-        CSP_TS(2);
-        request_stats(load_rec(rec_of(it - 1)));
-        const PipeTask tn = load_rec(rec_of(it + 1));
-        KeyCursor kcn;
-        auto keys_next = [&](int first, int count) { request_keys_inside(tn, kcn, first, count); };   // this wavefront is done with its tiles
-        auto keys_next_ragged = [&]() { request_keys_ragged(tn); };
+            request_stats(load_rec(rec_of(it - 1)));
+            CSP_TS(3);
+        };
+        auto nothing = [&]() {};
+        if constexpr (REUSED) after_logits();
         const PipeTask tf = load_rec(rec_of(it));
-        CSP_TS(3);
-        if (tf.valid) front_a(pk, ref, win, tf, chunk_inside(tn), keys_next, keys_next_ragged);
-        else keys_next_ragged();
+        if (tf.valid) {
+            if constexpr (REUSED) front_a(pk, ref, win, tf, next_inside, keys_next, keys_next_ragged, nothing, nothing);
+            else front_a(pk, ref, win, tf, next_inside, keys_next, keys_next_ragged, first_tile_done, after_logits);
+        } else {
+            if constexpr (!REUSED) {
+                first_tile_done();
+                after_logits();
+            }
+            keys_next_ragged(kEarlyLoads, kLateLoads);
+        }
         CSP_TS(7);
         lds_barrier();   // every wavefront is done with the queries; its maxima and sums are in LDS
         CSP_TS(8);
@@ -816,7 +851,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         if (tf.valid) front_b(tf);
         CSP_TS(9);
         CSP_TSA(3);
-        wait_loads<kTileLoads + kQueryLoads>();   // the statistics and modalities of task it - 1 have landed
+        wait_loads<kLateLoads + kQueryLoads>();   // the statistics of task it - 1 have landed (younger: the later half of the keys, the queries)
         CSP_TS(10);
         CSP_TSA(1);
         {
@@ -842,16 +877,17 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         const PipeTask t = load_rec(rec_of(it));
         const int ncb = rec_chunks(t), own = t.c0 / kPipeChunk;
         auto no_keys = [&](int, int) {};
-        auto no_keys_ragged = [&]() {};
+        auto no_keys_ragged = [&](int, int) {};
+        auto nothing = [&]() {};
         for (int k = 0; k < ncb; ++k) {
             PipeTask ty = t;   // the chunks of a head part differ in their first key only
             ty.c0 = (k < ncb - 1 ? (k < own ? k : k + 1) : own) * kPipeChunk;
             lds_barrier();
             request_queries(ty);
-            request_keys_ragged(ty);
+            request_keys_ragged(ty, 0, kTileLoads);
             wait_loads<0>();
             lds_barrier();
-            front_a(pkA, refA, winA, ty, false, no_keys, no_keys_ragged);
+            front_a(pkA, refA, winA, ty, false, no_keys, no_keys_ragged, nothing, nothing);
             lds_barrier();
             front_b(ty);
         }
