@@ -5,8 +5,16 @@
 // sequence, attention weights over every cached key, then per-key sums over
 // the query axis split by whether query and key share a modality.
 //
-// Design.  The per-key sums need the final softmax normaliser of every window
-// row, which depends on all L keys, so the key stream is walked twice:
+// This file: the two-pass kernels (fp32 inputs, parts of the window beyond what
+// the single-read kernel takes, sequences too long for its resident set; the
+// second pass alone when the caller supplies the rows' normalisers), the ordered
+// sum of per-head score arrays of a selection group, the sizing rules
+// (score_plan) and launch_score, which hands every bf16 case that fits to the
+// single-read kernel of score_single.hip.
+//
+// Design of the two passes.  The per-key sums need the final softmax normaliser
+// of every window row, which depends on all L keys, so the key stream is walked
+// twice:
 //   pass A (score_stats_kernel)  : S = K Q^T on MFMA with queries on the lane
 //        axis, so the running (max, sum-exp) of a row lives in one lane and
 //        needs no cross-lane traffic inside the loop;

@@ -5,32 +5,47 @@
 // as in score.hip.
 //
 // Design.  The per-key sums need the final normaliser of every window row, which depends on all
-// L keys.  A task is a chunk of 512 keys of one (sequence, query head): the workgroup computes the
-// chunk's logits against the whole window (S = Q K^T on v_mfma_f32_32x32x16_bf16, keys on the
-// lane axis, 8 wavefronts x 2 tiles x 32 accumulator registers), publishes the chunk's
-// log-sum-exp per row, reads the ones of the other chunks of the head and turns its weights into
-// normalised ones.  The exchange costs a memory round trip or two; a kernel that sits out that
-// latency (and the latency of its first key tile) once per chunk runs at 45 % of the HBM rate.
-// Here it is hidden:
+// L keys.  A task is a chunk of 512 keys of one (sequence, query head, part of <= 64 window rows):
+// the workgroup computes the chunk's logits against the part (S^T = K Q^T on
+// v_mfma_f32_32x32x16_bf16, window rows on the lane axis, 8 wavefronts x 2 tiles of 32 keys),
+// publishes the chunk's log-sum-exp per row, reads the ones of the other chunks of the head and
+// turns its weights into normalised ones.  The exchange costs a memory round trip or two; a kernel
+// that sits out that latency (and the latency of its first key tile) once per chunk runs at 45 % of
+// the HBM rate.  Here it is hidden:
 //  - one workgroup of 8 wavefronts per compute unit, resident for the whole launch (all 160 KiB of
-//    LDS), two wavefronts per SIMD so that one computes while the other waits for LDS or a barrier;
-//    tasks are dealt statically (workgroup w takes tasks w, w + #workgroups, ...);
-//  - in step n a workgroup computes logits, statistics and the published log-sum-exp of task n
-//    ("front"), THEN merges the statistics of task n-1 - published one whole step ago by
-//    everybody - and writes its scores ("back"); the weights of task n-1 wait in registers as
-//    fp16 pairs meanwhile;
-//  - every global load of the loop goes straight to LDS (global_load_lds): the key tiles of task
-//    n+1 are requested as soon as the MFMAs of task n have read the tile buffer (XOR-swizzled
-//    rows: the LDS image is laid out by choosing each lane's global address), the queries of
-//    task n+1 once every wavefront is past those MFMAs, the statistics and key modalities of
-//    task n-1 at the start of the step.  No load holds a register, and each has most of a step
-//    to land.  The compiler does not order LDS reads against these loads: the waits are written
-//    by hand (s_waitcnt vmcnt with the number of younger loads; loads return in order).
-// A memory-side model of this schedule (same bytes in flight, the compute replaced by a delay)
-// sustains 5.9 / 5.4 / 4.7 TB/s with 3 / 4 / 5 us of compute per chunk and compute unit.
+//    LDS), two wavefronts per SIMD; tasks are dealt statically (workgroup w takes tasks w,
+//    w + #workgroups, ...) from a table of 64-byte records that a set-up kernel writes per launch and
+//    the pipeline reads through the scalar cache;
+//  - three tasks are in flight per workgroup.  In step n: the logits of task n; the scores of task
+//    n-2 (its weights have waited in registers as fp16 pairs, its rows' log-sum-exps in LDS since
+//    the last step); maxima, weights and row sums of task n and, after a barrier, its published
+//    log-sum-exp; THEN the merge of the statistics of task n-1, published most of a step ago by
+//    everybody.  Two workgroup barriers per step;
+//  - the vector ALU does one FMA, one exponential and two conversions per weight and little else.
+//    With the window rows on the lane axis a row's maximum is an in-lane reduction (plus one
+//    exchange with the lane 32 further on); the row sums are an MFMA of the fp16 weights with a
+//    matrix of ones (the contraction runs over a lane's registers, i.e. over keys); an MFMA with a
+//    permutation matrix hands every weight, unchanged, to the lane of its key, which is the layout
+//    in which the column sums are again an MFMA (contraction over the window rows, the rows'
+//    factors 2^(reference - lse) as the other operand, split by the rows' modality);
+//  - every global load of the loop goes straight to LDS (global_load_lds, issued from inline
+//    assembly): the key tiles of task n+1 are requested as soon as the MFMAs of task n have read a
+//    tile buffer and from then on a few at a time between the exponentials (XOR-swizzled rows: the
+//    LDS image is laid out by choosing each lane's global address), the queries of task n+1 once
+//    every wavefront is past those MFMAs, the statistics of task n-1 behind the scores of task n-2.
+//    No load holds a register.  The compiler knows nothing of these loads (had it known, it would
+//    drain them all, s_waitcnt vmcnt(0), in front of every LDS access and barrier): the waits are
+//    written by hand (s_waitcnt vmcnt with the number of younger loads; loads return in order), and
+//    the workgroup barriers wait for LDS traffic only.
+// What bounds it: the key tiles have one buffer (the LDS is full), so a tile can be requested only
+// after the step's logits and must have landed before the next step's: all workgroups ask for
+// their 128 KiB in the same two thirds of a step, and the step is about as long as the memory
+// system needs for that plus the logits.  Shortening the arithmetic does not shorten the step
+// (measured); requesting earlier does, up to the point where the requests queue at the memory
+// pipeline and hold up the wavefront that issues them.
 // The exchange uses agent-scope stores and loads (sc1; no release fence: on this multi-XCD part
-// it would write back a whole L2).  Every statistic is set to NaN before the launch, so a value
-// that reads as a number has been published: entries validate themselves.
+// it would write back a whole L2).  Every statistic is set to NaN before the launch (set-up
+// kernel), so a value that reads as a number has been published: entries validate themselves.
 // No workgroup depends on one that has not started: the statistics of task n are published
 // before anything of task n-1 is waited for, and the chunks of a head are at most one step
 // apart (the host guarantees G * parts * chunks <= #workgroups), so every wait ends once all
@@ -38,7 +53,8 @@
 // bounded all the same (the chip may be shared, compute units may be masked): a workgroup whose
 // wait runs out notes the task, and when its own list is done recomputes the statistics of every
 // chunk of that head by itself with the very same code (same order of operations: the result is
-// bit-identical to the exchanged one) and finishes the task.  Such tasks are counted.
+// bit-identical to the exchanged one) and finishes the task.  Such tasks are counted
+// (ScoreParams::counters[0]).
 #include "score_tiles.h"
 
 // no implicit fusing of a*b+c: the two places that compute a chunk's statistics (the pipeline
