@@ -94,26 +94,37 @@ hipError_t launch_compact(const CompactParams& p, int row_bytes, hipStream_t s) 
 }
 
 // ---- measurement aid: the rate at which this device streams a buffer --------------------------
-// Every lane reads 16 bytes at a time (non-temporal), 4 reads in flight, workgroups stride over
-// the buffer; the data is copied to dst, or, with dst == nullptr, folded into one word per
-// workgroup (so that the reads are not optimised away) that is written to sink.
+// Every lane reads 16 bytes at a time (non-temporal), 4 reads in flight, a few resident workgroups per
+// compute unit take 16 KiB blocks of the buffer round-robin; the data is copied to dst, or, with
+// dst == nullptr, folded into one word per workgroup (so that the reads are not optimised away) that
+// is written to sink.
 namespace {
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
-__global__ __launch_bounds__(256) void probe_stream_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n16, uint32_t* sink) {
-    const size_t stride = (size_t)gridDim.x * 256;
+// Launch shape as measured on MI355X (2 GiB): 4-wavefront workgroups, 4 loads of 16 bytes in flight
+// per lane; 2 workgroups per compute unit read fastest (7.3 TB/s; 1 x 8 wavefronts 7.2, 4 x 4: 7.1,
+// 8 x 4: 6.7, 2 loads in flight: 6.3), 4 per compute unit copy fastest (5.6 TB/s read + write;
+// 2 x 4: 5.4, 1 x 8: 5.2).
+constexpr int kProbeThreads = 256, kProbeUnroll = 4;
+constexpr int kProbePerCuRead = 2, kProbePerCuCopy = 4;
+// A workgroup takes blocks of kProbeThreads * kProbeUnroll * 16 bytes round-robin; within a block
+// load u of lane l is piece u * kProbeThreads + l (every instruction of a wavefront reads 1 KiB of
+// consecutive bytes).
+__global__ __launch_bounds__(kProbeThreads) void probe_stream_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n16, uint32_t* sink) {
+    constexpr size_t kBlock = (size_t)kProbeThreads * kProbeUnroll;
     uint32_t acc = 0;
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        u32x4_t a[4];
+    const size_t n_full = n16 / kBlock;
+    for (size_t blk = blockIdx.x; blk < n_full; blk += gridDim.x) {
+        const size_t i = blk * kBlock + threadIdx.x;
+        u32x4_t a[kProbeUnroll];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) a[u] = __builtin_nontemporal_load(src + i + u * stride);
+        for (int u = 0; u < kProbeUnroll; ++u) a[u] = __builtin_nontemporal_load(src + i + u * kProbeThreads);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (dst) __builtin_nontemporal_store(a[u], dst + i + u * stride);
+        for (int u = 0; u < kProbeUnroll; ++u) {
+            if (dst) __builtin_nontemporal_store(a[u], dst + i + u * kProbeThreads);
             else acc ^= a[u].x ^ a[u].y ^ a[u].z ^ a[u].w;
         }
     }
-    for (; i < n16; i += stride) {
+    for (size_t i = n_full * kBlock + (size_t)blockIdx.x * kProbeThreads + threadIdx.x; i < n16; i += (size_t)gridDim.x * kProbeThreads) {
         const u32x4_t a = __builtin_nontemporal_load(src + i);
         if (dst) __builtin_nontemporal_store(a, dst + i);
         else acc ^= a.x ^ a.y ^ a.z ^ a.w;
@@ -126,8 +137,10 @@ __global__ __launch_bounds__(256) void probe_stream_kernel(const u32x4_t* __rest
 }  // namespace
 
 hipError_t launch_probe_stream(const void* src, void* dst, size_t bytes, uint32_t* sink, hipStream_t s) {
-    hipLaunchKernelGGL(probe_stream_kernel, dim3(256 * 16), dim3(256), 0, s, reinterpret_cast<const u32x4_t*>(src),
-                       reinterpret_cast<u32x4_t*>(dst), bytes / 16, sink);
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    hipLaunchKernelGGL(probe_stream_kernel, dim3((unsigned)(cus * (dst ? kProbePerCuCopy : kProbePerCuRead))), dim3(kProbeThreads), 0, s,
+                       reinterpret_cast<const u32x4_t*>(src), reinterpret_cast<u32x4_t*>(dst), bytes / 16, sink);
     return hipGetLastError();
 }
 

@@ -120,6 +120,11 @@ def test_null_pointers_and_workspace(P):
     assert L.csp_decode_step_phase(d.ref(), 3, FAKE, FAKE, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, 2064, FAKE, FAKE, FAKE, 1 << 30, None) == -1
     assert L.csp_decode_step(d.ref(), FAKE, None, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, 2064, FAKE, FAKE, FAKE, 1 << 30, None) == -1
     assert L.csp_append_kv(d.ref(), FAKE, FAKE, FAKE, FAKE, 8 * 2064 * 128, 2064 * 128, 128, 0, FAKE, None) == -1
+    assert L.csp_probe_stream(None, None, 1 << 20, FAKE, None) == -1
+    assert L.csp_probe_stream(FAKE, None, 1 << 20, None, None) == -1
+    assert L.csp_probe_stream(FAKE, None, (1 << 20) + 8, FAKE, None) == -1                      # not a multiple of 16
+    assert L.csp_probe_stream(FAKE, FAKE + 4, 1 << 20, FAKE, None) == -1                        # misaligned dst
+    assert L.csp_probe_stream(FAKE, None, 0, FAKE, None) == -1
 
 
 def test_budget_below_recent_is_rejected(P):

@@ -684,6 +684,30 @@ def test_determinism(gpu):
     assert torch.equal(a[2].view(torch.int16), dc.layer.k_cache.view(torch.int16))
 
 
+def test_probe_stream_copies_and_reads(gpu):
+    """The measurement aid behind bench.py's read and copy ceilings: a copy is exact for sizes that are
+    whole blocks, ragged, and smaller than one block, and touches nothing behind the end; a read-only
+    pass leaves its XOR of the data in the sink."""
+    import paper_2412_04652_amd as pkg
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev); g.manual_seed(5)
+    for nbytes in (16, 4096, 16384 * 7, 16384 * 1024 + 16 * 37, (1 << 26) + 48):
+        src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=dev, generator=g)
+        whole = torch.full((nbytes + 256,), 0xA5, dtype=torch.uint8, device=dev)
+        sink = torch.zeros(4096, dtype=torch.uint8, device=dev)
+        pkg.csp_probe_stream(src, whole[:nbytes], sink)
+        torch.cuda.synchronize()
+        assert torch.equal(whole[:nbytes], src), nbytes
+        assert bool((whole[nbytes:] == 0xA5).all()), nbytes
+        assert not sink.any()
+        pkg.csp_probe_stream(src, None, sink)
+        torch.cuda.synchronize()
+        words = src.view(torch.int32)
+        x = int(np.bitwise_xor.reduce(words.cpu().numpy().view(np.uint32)))
+        got = int(np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)))
+        assert got == x, nbytes
+
+
 def test_guard_bands_notice_a_stray_write(gpu, oracle):
     """The guard bands that every GPU test puts around a layer's buffers (tests/conftest.py): a byte
     written just outside a buffer (here by the test itself, inside its own allocation) is reported."""
