@@ -18,7 +18,8 @@
 // with the lower-index-first tie rule, and without atomics on the output.  With
 // a single-modality window every key belongs to exactly one region: one bit
 // pattern per key stays in registers for all passes when the sequence fits one
-// super-block.
+// super-block (up to 32 keys per thread: 32K keys; measured at 32K keys 39 us
+// against 50 us with super-blocks of 8K keys re-read per pass).
 #include "csp_internal.h"
 
 namespace csp {
@@ -86,23 +87,29 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
     constexpr int SUPER = kSelThreads * ITEMS;
     const int n_super = CACHED ? 1 : (c.L + SUPER - 1) / SUPER;
 
+    static_assert(ITEMS <= 64, "a bit per item in a 64-bit mask");
+    typedef uint64_t ItemMask;          // a bit per item of this thread
     uint32_t ka[ITEMS];                 // self-region pattern, or the key's only pattern
     uint32_t kb[DUAL ? ITEMS : 1];      // cross-region pattern (DUAL only)
-    uint32_t in_cross = 0u;             // !DUAL: bit i set = key i ranks in the cross region
+    ItemMask in_cross = 0u;             // !DUAL: bit i set = key i ranks in the cross region
 
     const int lane = tid & 63, wave = tid >> 6;
     // key i of this lane in super-block sb
     auto key_index = [&](int sb, int i) { return sb * SUPER + wave * (ITEMS * kWave) + i * kWave + lane; };
     auto load_keys = [&](int sb) {
-        uint8_t m[ITEMS];
-#pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            const int j = key_index(sb, i);
-            m[i] = c.mod[j < c.P ? j : 0];   // every lane loads (a clamped index): no load under a branch
-        }
         in_cross = 0u;
+        // (in groups of 16 items: what is in flight at once fits the registers also with 32 items per thread)
+        constexpr int GROUP = ITEMS < 16 ? ITEMS : 16;
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
+        for (int g0 = 0; g0 < ITEMS; g0 += GROUP) {
+        uint8_t m[GROUP];
+#pragma unroll
+        for (int i = g0; i < g0 + GROUP; ++i) {
+            const int j = key_index(sb, i);
+            m[i - g0] = c.mod[j < c.P ? j : 0];   // every lane loads (a clamped index): no load under a branch
+        }
+#pragma unroll
+        for (int i = g0; i < g0 + GROUP; ++i) {
             const int j = key_index(sb, i);
             if constexpr (DUAL) {
                 ka[i] = j < c.P ? __float_as_uint(c.sc_self[j]) : kNone;
@@ -113,10 +120,11 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
                 // address waits for the modality would add a memory round trip to a latency-bound kernel
                 const int jc = j < c.P ? j : 0;
                 const uint32_t ss = __float_as_uint(c.sc_self[jc]), sx = __float_as_uint(c.sc_cross[jc]);
-                const bool self_key = m[i] ? c.has1 : c.has0;
+                const bool self_key = m[i - g0] ? c.has1 : c.has0;
                 ka[i] = j < c.P ? (self_key ? ss : sx) : kNone;
-                if (!self_key) in_cross |= 1u << i;
+                if (!self_key) in_cross |= (ItemMask)1 << i;
             }
+        }
         }
     };
     // region r pattern of key i (kNone if key i is not a candidate of region r)
@@ -237,14 +245,14 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         if (!CACHED) load_keys(sb);
         // 1. equals of each region held by this wavefront
         uint32_t eqw[2] = {0u, 0u};
-        uint32_t eq_any = 0u;  // bit i: some lane's key i equals a threshold (ties are rare: fast path below)
+        ItemMask eq_any = 0u;  // bit i: some lane's key i equals a threshold (ties are rare: fast path below)
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const uint64_t b0 = __ballot(pat(i, 0) == th_bits[0]);
             const uint64_t b1 = __ballot(pat(i, 1) == th_bits[1]);
             eqw[0] += __popcll(b0);
             eqw[1] += __popcll(b1);
-            eq_any |= ((b0 | b1) != 0ull ? 1u : 0u) << i;
+            eq_any |= (ItemMask)((b0 | b1) != 0ull ? 1u : 0u) << i;
         }
         uint64_t before, all;
         wave_exchange((uint64_t)eqw[0] | ((uint64_t)eqw[1] << 32), before, all);
@@ -252,7 +260,8 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
         base_eq[0] += (uint32_t)all;
         base_eq[1] += (uint32_t)(all >> 32);
         // 2. keep flags in key order (items ascend within the wavefront, lanes within an item)
-        uint32_t keep_bits = 0u, keep_w = 0u, both_w = 0u;
+        ItemMask keep_bits = 0u;
+        uint32_t keep_w = 0u, both_w = 0u;
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             const int j = key_index(sb, i);
@@ -268,7 +277,7 @@ __device__ __forceinline__ void select_body(const SelCtx& c, SelShared& sh) {
                 run[1] += __popcll(b1);
             }
             const bool keep = kp0 || kp1 || (j >= c.P && j < c.L);   // the last R keys are always kept
-            keep_bits |= (keep ? 1u : 0u) << i;
+            keep_bits |= (ItemMask)(keep ? 1u : 0u) << i;
             keep_w += __popcll(__ballot(keep));
             if constexpr (DUAL) both_w += __popcll(__ballot(kp0 && kp1));
         }
@@ -327,7 +336,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(SelectParams p) {
     } else if (c.L <= kSelThreads * ITEMS) {
         select_body<ITEMS, false, true>(c, sh);   // one super-block, patterns stay in registers
     } else {
-        select_body<8, false, false>(c, sh);      // long sequence: super-blocks re-read per pass
+        select_body<8, false, false>(c, sh);      // longer than 32K keys: super-blocks re-read per pass
     }
 }
 
@@ -344,7 +353,9 @@ hipError_t launch_select(const SelectParams& p, int max_seqlen, hipStream_t s) {
     };
     if (items <= 4) return launch(select_kernel<4>);
     if (items <= 8) return launch(select_kernel<8>);
-    return launch(select_kernel<16>);  // longer than 16K keys: several super-blocks
+    if (items <= 16) return launch(select_kernel<16>);
+    return launch(select_kernel<32>);  // up to 32K keys stay in registers; beyond: several super-blocks (64 keys per thread
+                                       // spill, and at 64K keys the re-reads are not what takes the time)  // up to 64K keys stay in registers (64 per thread); beyond: several super-blocks
 }
 
 }  // namespace csp

@@ -264,6 +264,36 @@ def test_select_bit_exact(gpu, oracle, ratio, quantise):
             assert cnt[b, s, 1:].tolist() == [rc["K_s"], rc["K_c"], rc["both"]]
 
 
+@pytest.mark.parametrize("L", [16384, 16385, 24000, 32768, 32769])
+def test_select_bit_exact_long(gpu, oracle, L):
+    """Lengths around the edges of the kernel instances that keep 16 and 32 keys per thread in
+    registers, and just beyond (super-blocks re-read per pass): indices and counts bit for bit, with
+    quantised scores so that the thresholds tie."""
+    from paper_2412_04652_amd.runner import CspLayer
+    rng = np.random.default_rng(L)
+    O, R, T = 64, 48, L // 3
+    lens = [(L, "mixed"), (L - 1000, "text")]
+    cu = np.concatenate([[0], np.cumsum([l for l, _ in lens])])
+    mods, ss, cc = _select_inputs(rng, lens, O, 500)
+    mod = np.concatenate(mods)
+    _say(f"[select long] L={L} T={T}")
+    layer = CspLayer(dtype="bf16", H_q=1, H_kv=1, D=128, O=O, R=R, cu_seqlens=cu.tolist(), budgets=[T, T], cross_ratio=0.3)
+    d_self = torch.from_numpy(np.concatenate(ss)[None]).to(gpu)
+    d_cross = torch.from_numpy(np.concatenate(cc)[None]).to(gpu)
+    layer.select(torch.from_numpy(mod).to(gpu), score_self=d_self, score_cross=d_cross)
+    torch.cuda.synchronize()
+    idx = layer.kept_idx.cpu().numpy()
+    cnt = layer.kept_cnt.cpu().numpy()
+    for b, (Lb, _) in enumerate(lens):
+        lo = int(cu[b])
+        ref, rc = oracle.select(ss[b], cc[b], mod[lo:lo + Lb], O, R, T, 0.3)
+        n = int(cnt[b, 0, 0])
+        assert n == rc["kept"], (b, n, rc)
+        np.testing.assert_array_equal(idx[b, 0, :n], ref)
+        assert (idx[b, 0, n:] == -1).all()
+        assert cnt[b, 0, 1:].tolist() == [rc["K_s"], rc["K_c"], rc["both"]]
+
+
 def test_select_skewed_scores_64k(gpu, oracle):
     """64k keys, scores clustered in a few exponents with a heavy tail (radix skew)."""
     from paper_2412_04652_amd.runner import CspLayer
