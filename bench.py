@@ -628,16 +628,19 @@ def main():
     step_share = {k: v["ms"] * (n_layers * (decode_steps if k.startswith("decode") else 1)) for k, v in kern.items()}
     dom = max(step_share, key=step_share.get)
     # measured HBM traffic per launch of that kernel (rocprofv3 --pmc, see profiles/), if recorded
-    traffic = None
+    # (a stored figure: `traffic_commit` names the commit of the library it was measured on)
+    traffic, traffic_commit = None, None
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
-            rec = json.load(f).get(f"{args.workload}@{args.budget:g}", {}).get(dom.split("(")[0])
+            stored = json.load(f)
+        rec = stored.get(f"{args.workload}@{args.budget:g}", {}).get(dom.split("(")[0])
         if rec:
             traffic = rec["fetch_bytes"] + rec["write_bytes"]
+            traffic_commit = stored.get("commit")
     except (OSError, ValueError, KeyError):
         traffic = None
     roof = dict(bound="hbm", kernel=dom, achieved=kern[dom]["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                frac=kern[dom]["gbps"] / HBM_PEAK_GBPS, traffic=traffic,
+                frac=kern[dom]["gbps"] / HBM_PEAK_GBPS, traffic=traffic, traffic_commit=traffic_commit,
                 algorithmic_bytes_per_launch=kern[dom]["bytes"], avg_launch_ms=kern[dom]["ms"])
     out = {
         "metric": "pruned KV tokens/sec (score+select+compact) and decode attn HBM GB/s, 1 GPU",
