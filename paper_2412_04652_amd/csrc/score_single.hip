@@ -468,11 +468,13 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     };
 
     // ---- front stage: logits, statistics and the published log-sum-exp of the chunk ----------
-    // The chunk's keys and queries are in LDS.  When this wavefront has read its tiles for the last
-    // time it requests the next ones with next_keys(first, count), a few at a time between the
-    // exponentials (the memory pipeline takes a 1 KiB request every 16 cycles or so: requested in one
-    // go they would stall the wavefront for thousands of cycles); after_barrier() runs when every
-    // wavefront has read the queries.  (front_a: up to the per-wavefront maxima and sums in LDS; after a
+    // The chunk's keys and queries are in LDS.  When this wavefront has read a tile for the last time
+    // it may request the next task's: first_tile_done() is called after the MFMAs of the first tile
+    // (streamed keys) or of both, after_logits() when the logits are complete, and next_keys(first,
+    // count) a few requests at a time between the exponentials (the memory pipeline takes a 1 KiB
+    // request every 16 cycles or so: requested in one go they would stall the wavefront for thousands
+    // of cycles), or next_keys_ragged(first, count) in one go in front of them where the next chunk is
+    // the ragged end of a sequence.  (front_a: up to the per-wavefront maxima and sums in LDS; after a
     // workgroup barrier front_b publishes the chunk's log-sum-exp.)
     // On return pk holds the chunk's weights 2^15 * 2^(c*logit - wavefront maximum of the row) as fp16
     // pairs (pk[t4][mb][h]: accumulator registers 2h, 2h+1 of tile t4, query block mb), ref this
@@ -794,9 +796,10 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
     };
 
     // ---- the pipeline -------------------------------------------------------------------------
-    // Loads of a step, in issue order (per wavefront): statistics + modalities of the back task,
-    // key tiles of the next front task (kTileLoads), its queries (kQueryLoads).  Two workgroup
-    // barriers per step: at its start and between the halves of the two stages.
+    // Loads of a step, in issue order (per wavefront): the first kEarlyLoads of the next task's key
+    // tiles, the statistics of the task one step back, the other kLateLoads of the key tiles, the
+    // next task's queries (kQueryLoads).  Two workgroup barriers per step: at its start and between
+    // the halves of the front stage.
     f16x2 pkA[NT][NQB][8], pkB[NT][NQB][8];
     float refA = 0.f, refB = 0.f;
     WindowBits winA = 0u, winB = 0u;
@@ -809,10 +812,10 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         request_keys_ragged(t0, 0, kTileLoads);
         wait_loads<0>();
     }
-    // One step, for the tasks it, it - 1 and it - 2 of this workgroup: the scores of task it - 2 from
-    // its waiting weights and the log-sum-exps merged in the previous step; logits, weights, maxima
-    // and sums of task it; barrier; its log-sum-exp published; the published ones of task it - 1
-    // merged.  What a workgroup publishes in a step is looked for by the others in their next step,
+    // One step, for the tasks it, it - 1 and it - 2 of this workgroup: logits of task it; the scores of
+    // task it - 2 from its waiting weights and the log-sum-exps merged in the previous step (reused
+    // keys: the scores first); maxima, weights and sums of task it; barrier; its log-sum-exp
+    // published; the published ones of task it - 1 merged.  What a workgroup publishes in a step is looked for by the others in their next step,
     // after they have published their own: they may be most of a step apart without anybody waiting.
     // The weights of a task are consumed right before the registers are filled with those of the task
     // two steps on.  Records are fetched where they are needed (a scalar load each) rather than
