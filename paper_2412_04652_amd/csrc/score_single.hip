@@ -23,8 +23,9 @@
 //    everybody.  Two workgroup barriers per step;
 //  - the vector ALU does one FMA, one exponential and two conversions per weight and little else.
 //    With the window rows on the lane axis a row's maximum is an in-lane reduction (plus one
-//    exchange with the lane 32 further on); the row sums are an MFMA of the fp16 weights with a
-//    matrix of ones (the contraction runs over a lane's registers, i.e. over keys); an MFMA with a
+//    exchange with the lane 32 further on); the row sums are MFMAs of the fp16 weights with a
+//    matrix of ones (v_mfma_f32_4x4x4_16b_f16: the contraction runs over a lane's registers, i.e.
+//    over keys, and the small shape costs a quarter of the cycles and registers); an MFMA with a
 //    permutation matrix hands every weight, unchanged, to the lane of its key, which is the layout
 //    in which the column sums are again an MFMA (contraction over the window rows, the rows'
 //    factors 2^(reference - lse) as the other operand, split by the rows' modality);
@@ -223,8 +224,10 @@ __device__ __forceinline__ uint64_t load_bits64(const PipeTask& t, int pos) {
 __device__ __forceinline__ int rec_chunks(const PipeTask& t) { return (t.L + kPipeChunk - 1) / kPipeChunk; }
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr float kWeightShift = 15.f;   // weights are kept as 2^15 * 2^(x - maximum): the fp16 copies use the format's range
 // The factor of a row, 2^(reference - lse) <= 2^-15, enters the column-sum MFMAs as fp16 scaled by 2^30.
 constexpr float kFactorShift = 30.f;
@@ -580,24 +583,24 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
         }
         CSP_TS(5);
         // weights in place of the logits, as fp16 (half the registers; 11 bits are within the tolerance,
-        // and the scale keeps small weights normal).  Per block of 32 keys x 32 rows: the row sums are an
-        // MFMA of the block with a matrix of ones (the contraction runs over the block's keys), and an
+        // and the scale keeps small weights normal).  Per block of 32 keys x 32 rows: the row sums are
+        // MFMAs of the block with a matrix of ones (the contraction runs over a lane's registers: keys), and an
         // MFMA of the block with a permutation matrix hands every weight, unchanged, to the lane of its
         // key (the layout in which the back stage contracts over the window rows): what the vector ALU
         // does per weight is one FMA, one exponential and two conversions.
         auto weights = [&](auto interleave) {
             constexpr int kIters = NQB * NT * 4;
             const int lw = opaque(lane);
-            f16x8 ones, perm_lo, perm_hi;   // perm_lo/hi[e]: accumulator register e (8 + e) of this half is key lane%32 of the tile
+            const f16x4 ones = {(_Float16)1.f, (_Float16)1.f, (_Float16)1.f, (_Float16)1.f};
+            f16x8 perm_lo, perm_hi;   // perm_lo/hi[e]: accumulator register e (8 + e) of this half is key lane%32 of the tile
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                ones[e] = (_Float16)1.f;
                 perm_lo[e] = acc_row(e, lw >> 5) == (lw & 31) ? (_Float16)1.f : (_Float16)0.f;
                 perm_hi[e] = acc_row(8 + e, lw >> 5) == (lw & 31) ? (_Float16)1.f : (_Float16)0.f;
             }
 #pragma unroll
             for (int mb = 0; mb < NQB; ++mb) {
-                f32x16 sums;
+                f32x4 sums = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int t4 = 0; t4 < NT; ++t4) {
                     f16x2 wt[8];
@@ -619,8 +622,11 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
                     }
                     const f16x8 w_lo = __builtin_shufflevector(__builtin_shufflevector(wt[0], wt[1], 0, 1, 2, 3), __builtin_shufflevector(wt[2], wt[3], 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
                     const f16x8 w_hi = __builtin_shufflevector(__builtin_shufflevector(wt[4], wt[5], 0, 1, 2, 3), __builtin_shufflevector(wt[6], wt[7], 0, 1, 2, 3), 0, 1, 2, 3, 4, 5, 6, 7);
-                    sums = mma_f16(ones, w_lo, t4 == 0 ? zero : sums);
-                    sums = mma_f16(ones, w_hi, sums);
+                    // (v_mfma_f32_4x4x4_16b_f16: sixteen 4x4 products per instruction; with a matrix of ones on the
+                    // left every row of a lane's result is the sum of the lane's own four values)
+#pragma unroll
+                    for (int h = 0; h < 8; h += 2)
+                        sums = __builtin_amdgcn_mfma_f32_4x4x4f16(ones, __builtin_shufflevector(wt[h], wt[h + 1], 0, 1, 2, 3), sums, 0, 0, 0);
                     f32x16 d = mma_f16(w_lo, perm_lo, zero);
                     d = mma_f16(w_hi, perm_hi, d);
 #pragma unroll
@@ -629,7 +635,7 @@ __global__ __launch_bounds__(kSThreads, 2) void score_single_kernel(ScoreParams 
                         pk[t4][mb][h] = __builtin_convertvector(two, f16x2);
                     }
                 }
-                wsum[wave * NQ + mb * 32 + (lane & 31)] = sums[0];   // (every row of the product is the same)
+                wsum[wave * NQ + mb * 32 + (lane & 31)] = halves_allreduce<false>(sums[0]);   // (the lane 32 further on has the row's other keys)
             }
         };
         if (next_inside) {
